@@ -1,0 +1,430 @@
+/*
+ * ygg_oracle.c -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, fp64 CPU statement of what the tree-verification hot path of
+ * Yggdrasil computes.  Only tests, the smoke check and the CPU-baseline leg of
+ * the benchmark may call it; the GPU library never does, and the two share no
+ * code.  Every function is the definition written out (nothing is blocked,
+ * fused or re-ordered), so it can be checked against the paper by eye:
+ *
+ *   attention : a speculative token tree is verified in one parallel pass in
+ *               which the attention mask encodes the tree's causal
+ *               dependency (paper Sec. 2 "Source of Improvements", Sec. 4.2
+ *               last paragraph): node i sees the confirmed prefix, its
+ *               ancestors and itself.
+ *   expand    : equal-growth drafting adds exactly W_draft leaves per draft
+ *               step, chosen by largest path-wise gain with the drafter's
+ *               generation probabilities as acceptance surrogates (Sec. 4.2
+ *               "Draft Width Selection").  Reading used here: candidates are
+ *               children of the previous depth's nodes, score = cumulative
+ *               natural-log softmax probability along the path.
+ *   accept    : the draft is accepted where it matches the verifier's own
+ *               greedy token (Sec. 1; Sec. 5 "accept speculation management"),
+ *               the verifier's token after the last accepted node is the bonus
+ *               token (Sec. 4.1, text under Eq. 2), and the accepted nodes'
+ *               K/V become part of the contiguous cache (Sec. 6, TokenTree).
+ *
+ * Pins (tests/test_oracle_*.py): per-path sequential attention, width-1 ==
+ * causal attention via a library routine, closed forms (q = 0, constant V,
+ * L = 0), split/merge identity, brute-force top-W and path enumeration,
+ * hand-worked fixtures under tests/golden/.
+ *
+ * Element types: 0 = fp32, 1 = bf16 (stored as uint16, upper half of an fp32).
+ * All floating-point work is done in double.  Return value 0 = ok, negative =
+ * invalid argument (see the checks at the top of each function).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+
+static size_t elem_bytes(int dtype) { return dtype == ORC_F32 ? 4u : 2u; }
+
+static double load_elem(const void *base, int dtype, int64_t idx)
+{
+    if (dtype == ORC_F32)
+        return (double)((const float *)base)[idx];
+    uint16_t h = ((const uint16_t *)base)[idx];
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* parent[0] == -1 and 0 <= parent[i] < i for i > 0 */
+static int tree_is_topological(const int32_t *parent, int32_t N)
+{
+    if (N < 1 || parent[0] != -1)
+        return 0;
+    for (int32_t i = 1; i < N; ++i)
+        if (parent[i] < 0 || parent[i] >= i)
+            return 0;
+    return 1;
+}
+
+static int32_t node_depth(const int32_t *parent, int32_t i)
+{
+    int32_t d = 0;
+    while (parent[i] >= 0) {
+        i = parent[i];
+        ++d;
+    }
+    return d;
+}
+
+/* ------------------------------------------------------------------------ *
+ * Tree-masked verify attention, one output row.
+ *
+ * Layouts: q [B,N,Hq,Dh]; k_cache,v_cache [B,cap,Hkv,Dh] with rows
+ * [0,seq_lens[b]) valid; k_tree,v_tree [B,N,Hkv,Dh]; parent_idx [B,N].
+ * Query head h uses kv head h / (Hq/Hkv).
+ *
+ * Key set of node i:  J(i) = prefix rows 0..L-1  U  {i, parent[i], ..., root}.
+ *   s_j = scale * <q_i, k_j>;  m = max_j s_j;  p_j = exp(s_j - m);
+ *   l = sum_j p_j;  out = sum_j (p_j / l) v_j;  lse = m + ln l.
+ * Keys outside J(i) are left out of every sum (never entered as -inf).
+ *
+ * probs (optional, length L + N): p_j / l for prefix key j at [j] and for tree
+ * node t at [L + t]; exactly 0.0 for nodes outside J(i).
+ * ------------------------------------------------------------------------ */
+int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int32_t Dh,
+                             int dtype, double scale, int64_t cap,
+                             const void *q, const void *k_cache, const void *v_cache,
+                             const int32_t *seq_lens, const void *k_tree, const void *v_tree,
+                             const int32_t *parent_idx,
+                             int32_t b, int32_t i, int32_t h,
+                             double *out_row /* [Dh] */, double *lse /* [1] or NULL */,
+                             double *probs /* [L+N] or NULL */)
+{
+    if (B < 1 || N < 1 || Hq < 1 || Hkv < 1 || Dh < 1 || Hq % Hkv != 0)
+        return -1;
+    if (b < 0 || b >= B || i < 0 || i >= N || h < 0 || h >= Hq)
+        return -2;
+    const int32_t *parent = parent_idx + (int64_t)b * N;
+    if (!tree_is_topological(parent, N))
+        return -3;
+    const int32_t L = seq_lens[b];
+    if (L < 0 || (int64_t)L > cap)
+        return -4;
+
+    const int32_t G = Hq / Hkv;
+    const int32_t hk = h / G;
+    const int64_t q_off = (((int64_t)b * N + i) * Hq + h) * Dh;
+
+    char *visible = (char *)calloc((size_t)N, 1);
+    double *s = (double *)malloc(sizeof(double) * (size_t)(L + N));
+    if (!visible || !s) {
+        free(visible);
+        free(s);
+        return -5;
+    }
+    for (int32_t a = i; a >= 0; a = parent[a])
+        visible[a] = 1;
+
+    /* scores */
+    double m = -INFINITY;
+    for (int32_t j = 0; j < L; ++j) {
+        const int64_t k_off = (((int64_t)b * cap + j) * Hkv + hk) * Dh;
+        double dot = 0.0;
+        for (int32_t d = 0; d < Dh; ++d)
+            dot += load_elem(q, dtype, q_off + d) * load_elem(k_cache, dtype, k_off + d);
+        s[j] = scale * dot;
+        if (s[j] > m)
+            m = s[j];
+    }
+    for (int32_t t = 0; t < N; ++t) {
+        if (!visible[t])
+            continue;
+        const int64_t k_off = (((int64_t)b * N + t) * Hkv + hk) * Dh;
+        double dot = 0.0;
+        for (int32_t d = 0; d < Dh; ++d)
+            dot += load_elem(q, dtype, q_off + d) * load_elem(k_tree, dtype, k_off + d);
+        s[L + t] = scale * dot;
+        if (s[L + t] > m)
+            m = s[L + t];
+    }
+
+    /* softmax weights */
+    double l = 0.0;
+    for (int32_t j = 0; j < L; ++j) {
+        s[j] = exp(s[j] - m);
+        l += s[j];
+    }
+    for (int32_t t = 0; t < N; ++t) {
+        if (!visible[t]) {
+            s[L + t] = 0.0;
+            continue;
+        }
+        s[L + t] = exp(s[L + t] - m);
+        l += s[L + t];
+    }
+
+    /* weighted sum of values */
+    for (int32_t d = 0; d < Dh; ++d)
+        out_row[d] = 0.0;
+    for (int32_t j = 0; j < L; ++j) {
+        const int64_t v_off = (((int64_t)b * cap + j) * Hkv + hk) * Dh;
+        const double w = s[j] / l;
+        for (int32_t d = 0; d < Dh; ++d)
+            out_row[d] += w * load_elem(v_cache, dtype, v_off + d);
+    }
+    for (int32_t t = 0; t < N; ++t) {
+        if (!visible[t])
+            continue;
+        const int64_t v_off = (((int64_t)b * N + t) * Hkv + hk) * Dh;
+        const double w = s[L + t] / l;
+        for (int32_t d = 0; d < Dh; ++d)
+            out_row[d] += w * load_elem(v_tree, dtype, v_off + d);
+    }
+    if (lse)
+        *lse = m + log(l);
+    if (probs)
+        for (int32_t j = 0; j < L + N; ++j)
+            probs[j] = s[j] / l;
+
+    free(visible);
+    free(s);
+    return 0;
+}
+
+/* All rows: out [B,N,Hq,Dh] and lse [B,N,Hq] (lse may be NULL), in double. */
+int ygg_oracle_tree_attention(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int32_t Dh,
+                              int dtype, double scale, int64_t cap,
+                              const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *seq_lens, const void *k_tree, const void *v_tree,
+                              const int32_t *parent_idx, double *out, double *lse)
+{
+    if (B < 1 || N < 1 || Hq < 1 || Hkv < 1 || Dh < 1 || Hq % Hkv != 0)
+        return -1;
+    int rc = 0;
+    const int64_t rows = (int64_t)B * N * Hq;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t r = 0; r < rows; ++r) {
+        const int32_t h = (int32_t)(r % Hq);
+        const int32_t i = (int32_t)((r / Hq) % N);
+        const int32_t b = (int32_t)(r / ((int64_t)Hq * N));
+        int e = ygg_oracle_attention_row(B, N, Hq, Hkv, Dh, dtype, scale, cap, q, k_cache, v_cache,
+                                         seq_lens, k_tree, v_tree, parent_idx, b, i, h,
+                                         out + r * Dh, lse ? lse + r : NULL, NULL);
+        if (e != 0) {
+#pragma omp critical
+            rc = e;
+        }
+    }
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ *
+ * Equal-growth expansion.
+ *
+ * Depth-d nodes live at indices base_d = 1 + (d-1) W ... base_d + W - 1; the
+ * root is node 0.  The frontier feeding depth d is the root (F = 1) for d = 1
+ * and the W nodes of depth d-1 otherwise; logits row p belongs to frontier
+ * node p.
+ *
+ *   lse_p  = ln sum_v exp(x[p,v])                      (max-subtracted)
+ *   s(p,v) = cum[frontier p] + (x[p,v] - lse_p)
+ * ------------------------------------------------------------------------ */
+int ygg_oracle_expand_scores(int32_t F, int32_t V, const float *logits /* [F,V] */,
+                             const float *cum_front /* [F] */, double *scores /* [F,V] */)
+{
+    if (F < 1 || V < 1)
+        return -1;
+    for (int32_t p = 0; p < F; ++p) {
+        const float *x = logits + (int64_t)p * V;
+        double mx = -INFINITY;
+        for (int32_t v = 0; v < V; ++v)
+            if ((double)x[v] > mx)
+                mx = (double)x[v];
+        double sum = 0.0;
+        for (int32_t v = 0; v < V; ++v)
+            sum += exp((double)x[v] - mx);
+        const double lse = mx + log(sum);
+        for (int32_t v = 0; v < V; ++v)
+            scores[(int64_t)p * V + v] = (double)cum_front[p] + ((double)x[v] - lse);
+    }
+    return 0;
+}
+
+typedef struct {
+    double s;
+    int64_t flat; /* p * V + v */
+} cand_t;
+
+/* higher score first; equal scores: lower flat index first */
+static int cand_cmp(const void *a, const void *b)
+{
+    const cand_t *x = (const cand_t *)a, *y = (const cand_t *)b;
+    if (x->s > y->s)
+        return -1;
+    if (x->s < y->s)
+        return 1;
+    if (x->flat < y->flat)
+        return -1;
+    if (x->flat > y->flat)
+        return 1;
+    return 0;
+}
+
+/*
+ * One draft step: all F*V candidates are scored and fully sorted; the first W
+ * become the nodes of depth d in that order.  draft_logits [B,F,V];
+ * parent_idx, token_ids, cum_logprob [B,N] with N = 1 + D*W (depth d-1 slots
+ * are read, depth d slots are written; cum_logprob rounds the double score to
+ * fp32 once).  margin[b] (optional) = score gap between the W-th and (W+1)-th
+ * candidate (+inf if there is no (W+1)-th).
+ */
+int ygg_oracle_expand(int32_t B, int32_t D, int32_t W, int32_t V, int32_t d,
+                      const float *draft_logits, int32_t *parent_idx, int32_t *token_ids,
+                      float *cum_logprob, double *margin)
+{
+    if (B < 1 || D < 1 || W < 1 || V < 1 || d < 1 || d > D)
+        return -1;
+    const int32_t N = 1 + D * W;
+    const int32_t F = d == 1 ? 1 : W;
+    if ((int64_t)F * V < W)
+        return -2; /* fewer candidates than slots */
+    const int32_t base_prev = d == 1 ? 0 : 1 + (d - 2) * W;
+    const int32_t base_new = 1 + (d - 1) * W;
+    const int64_t C = (int64_t)F * V;
+
+    double *scores = (double *)malloc(sizeof(double) * (size_t)C);
+    cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)C);
+    float *cum_front = (float *)malloc(sizeof(float) * (size_t)F);
+    if (!scores || !cand || !cum_front) {
+        free(scores);
+        free(cand);
+        free(cum_front);
+        return -5;
+    }
+    for (int32_t b = 0; b < B; ++b) {
+        for (int32_t p = 0; p < F; ++p)
+            cum_front[p] = cum_logprob[(int64_t)b * N + base_prev + p];
+        ygg_oracle_expand_scores(F, V, draft_logits + (int64_t)b * C, cum_front, scores);
+        for (int64_t c = 0; c < C; ++c) {
+            cand[c].s = scores[c];
+            cand[c].flat = c;
+        }
+        qsort(cand, (size_t)C, sizeof(cand_t), cand_cmp);
+        for (int32_t k = 0; k < W; ++k) {
+            const int32_t p = (int32_t)(cand[k].flat / V);
+            const int32_t v = (int32_t)(cand[k].flat % V);
+            parent_idx[(int64_t)b * N + base_new + k] = base_prev + p;
+            token_ids[(int64_t)b * N + base_new + k] = v;
+            cum_logprob[(int64_t)b * N + base_new + k] = (float)cand[k].s;
+        }
+        if (margin)
+            margin[b] = C > W ? cand[W - 1].s - cand[W].s : INFINITY;
+    }
+    free(scores);
+    free(cand);
+    free(cum_front);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ *
+ * Greedy acceptance and K/V compaction.
+ *
+ *   t*[i]    = first index of the maximum of target_logits[i,:]
+ *              (or target_tokens[i] when the argmax is supplied)
+ *   match[0] = 1;  match[i] = match[parent[i]] && token_ids[i] == t*[parent[i]]
+ *   best     = matched node of greatest depth, lowest index among equals
+ *   path     = root ... best;  accept_len = depth(best) + 1;  bonus = t*[best]
+ *   every layer: cache[L_b + k] = tree[path[k]] for k < accept_len (K and V,
+ *   all kv heads, raw bytes);  seq_lens[b] = L_b + accept_len.
+ *
+ * target_logits [B,N,V] fp32 or NULL; target_tokens [B,N] or NULL (exactly one
+ * must be given); k_tree,v_tree [layers,B,N,Hkv,Dh]; k_cache,v_cache
+ * [layers,B,cap,Hkv,Dh]; accept_path [B,path_cols], -1 padded; tstar_out
+ * [B,N] optional.  Fails (-6) if the accepted path does not fit path_cols or
+ * the cache (L_b + accept_len > cap).
+ * ------------------------------------------------------------------------ */
+int ygg_oracle_accept_compact(int32_t B, int32_t N, int32_t V, int32_t path_cols,
+                              int32_t n_layers, int32_t Hkv, int32_t Dh, int dtype, int64_t cap,
+                              const float *target_logits, const int32_t *target_tokens,
+                              const int32_t *parent_idx, const int32_t *token_ids,
+                              const void *k_tree, const void *v_tree,
+                              void *k_cache, void *v_cache, int32_t *seq_lens,
+                              int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
+                              int32_t *tstar_out)
+{
+    if (B < 1 || N < 1 || path_cols < 1 || n_layers < 0)
+        return -1;
+    if ((target_logits == NULL) == (target_tokens == NULL))
+        return -2;
+    if (target_logits && V < 1)
+        return -2;
+
+    int32_t *tstar = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    char *match = (char *)malloc((size_t)N);
+    if (!tstar || !match) {
+        free(tstar);
+        free(match);
+        return -5;
+    }
+    int rc = 0;
+    const size_t row_bytes = (size_t)Hkv * (size_t)Dh * elem_bytes(dtype);
+
+    for (int32_t b = 0; b < B && rc == 0; ++b) {
+        const int32_t *parent = parent_idx + (int64_t)b * N;
+        const int32_t *token = token_ids + (int64_t)b * N;
+        if (!tree_is_topological(parent, N)) {
+            rc = -3;
+            break;
+        }
+        for (int32_t i = 0; i < N; ++i) {
+            if (target_tokens) {
+                tstar[i] = target_tokens[(int64_t)b * N + i];
+            } else {
+                const float *x = target_logits + ((int64_t)b * N + i) * V;
+                int32_t arg = 0;
+                for (int32_t v = 1; v < V; ++v)
+                    if (x[v] > x[arg])
+                        arg = v;
+                tstar[i] = arg;
+            }
+            if (tstar_out)
+                tstar_out[(int64_t)b * N + i] = tstar[i];
+        }
+        match[0] = 1;
+        int32_t best = 0, best_depth = 0;
+        for (int32_t i = 1; i < N; ++i) {
+            match[i] = match[parent[i]] && token[i] == tstar[parent[i]];
+            if (match[i]) {
+                const int32_t dep = node_depth(parent, i);
+                if (dep > best_depth) { /* strict: the lowest index wins ties */
+                    best_depth = dep;
+                    best = i;
+                }
+            }
+        }
+        const int32_t len = best_depth + 1;
+        const int32_t L = seq_lens[b];
+        if (len > path_cols || L < 0 || (int64_t)L + len > cap) {
+            rc = -6;
+            break;
+        }
+        for (int32_t k = 0; k < path_cols; ++k)
+            accept_path[(int64_t)b * path_cols + k] = -1;
+        for (int32_t a = best, k = len - 1; a >= 0; a = parent[a], --k)
+            accept_path[(int64_t)b * path_cols + k] = a;
+        accept_len[b] = len;
+        bonus_token[b] = tstar[best];
+
+        for (int32_t layer = 0; layer < n_layers; ++layer) {
+            for (int32_t k = 0; k < len; ++k) {
+                const int32_t node = accept_path[(int64_t)b * path_cols + k];
+                const size_t src = (((size_t)layer * B + b) * N + node) * row_bytes;
+                const size_t dst = (((size_t)layer * B + b) * (size_t)cap + (size_t)(L + k)) * row_bytes;
+                memcpy((char *)k_cache + dst, (const char *)k_tree + src, row_bytes);
+                memcpy((char *)v_cache + dst, (const char *)v_tree + src, row_bytes);
+            }
+        }
+        seq_lens[b] = L + len;
+    }
+    free(tstar);
+    free(match);
+    return rc;
+}
