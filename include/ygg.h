@@ -1,0 +1,157 @@
+/*
+ * ygg.h -- C ABI of the MI355X (gfx950) tree-verification library.
+ *
+ * Three operations make up one verification step of a static-shape, equal-growth
+ * draft token tree (Yggdrasil, arXiv 2512.23858):
+ *
+ *   ygg_equal_growth_expand   one draft step of the Equal-Growth Tree (Sec. 4.2)
+ *   ygg_tree_attention        tree-masked attention of the verifier pass (Sec. 2, Sec. 4.2)
+ *   ygg_accept_and_compact    acceptance of the matching draft path (Sec. 1, Sec. 5) and the
+ *                             TokenTree's K/V bookkeeping (Sec. 6), done on the device
+ *
+ * Conventions shared by every call
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the ygg_shape struct is HOST
+ *     memory and is only read during the call.  The library never allocates, frees or keeps
+ *     device memory; scratch space is the caller's `workspace` (size from ygg_workspace_bytes,
+ *     256-byte aligned, contents undefined on entry and on return).
+ *   - Calls only enqueue kernels on `hip_stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and never synchronise, so a sequence of calls can be captured in a HIP
+ *     graph.  All shapes are static: nothing on the host depends on device data.  This is the
+ *     static-runtime property the paper asks of the drafting algorithm (Sec. 3, Sec. 4.2).
+ *   - The return code reports host-checkable errors only (null pointers, inconsistent shape,
+ *     unsupported type, workspace too small, launch failure).  Data-dependent contract
+ *     violations (parent_idx not topological, seq_lens[b] > max_seq_len, NaN logits) are
+ *     undefined behaviour, except that no kernel reads or writes outside the buffers as
+ *     described by ygg_shape.
+ *   - Tensors are dense, row-major, token-major: [.., token, head, head_dim].
+ *   - Tree layout: node 0 is the root (the last confirmed token, whose K/V is not yet in the
+ *     cache); parent_idx[b][0] = -1 and 0 <= parent_idx[b][i] < i.  For the expansion call the
+ *     tree is level structured: depth d (1..D) occupies nodes 1+(d-1)W .. dW, N = 1 + D*W.
+ *     Attention and acceptance accept any topologically ordered tree of N nodes whose depth
+ *     does not exceed `depth`.
+ */
+#ifndef YGG_H
+#define YGG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    YGG_OK = 0,
+    YGG_ERR_NULL = 1,        /* a required pointer is NULL */
+    YGG_ERR_SHAPE = 2,       /* inconsistent or out-of-range shape field / argument */
+    YGG_ERR_UNSUPPORTED = 3, /* dtype / head_dim / size outside what the kernels implement */
+    YGG_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
+    YGG_ERR_LAUNCH = 5       /* the HIP runtime refused a launch */
+} ygg_status;
+
+typedef enum { YGG_F32 = 0, YGG_BF16 = 1 } ygg_dtype;
+
+typedef enum { YGG_OP_ATTENTION = 0, YGG_OP_EXPAND = 1, YGG_OP_ACCEPT = 2 } ygg_op;
+
+typedef struct {
+    int32_t batch;         /* B >= 1 sequences, one tree each */
+    int32_t n_q_heads;     /* Hq */
+    int32_t n_kv_heads;    /* Hkv, Hq % Hkv == 0; query head h uses kv head h / (Hq/Hkv) */
+    int32_t head_dim;      /* Dh: 64 or 128 */
+    int32_t depth;         /* D >= 0: number of draft steps = maximum node depth */
+    int32_t width;         /* W: nodes added per draft step (1..64) */
+    int32_t n_nodes;       /* N (1..1024); must equal 1 + D*W for ygg_equal_growth_expand */
+    int32_t vocab;         /* V (only used by expand / accept) */
+    int32_t kv_dtype;      /* ygg_dtype of Q, K, V and O */
+    float softmax_scale;   /* multiplies q.k; typically 1/sqrt(Dh) */
+    int64_t kv_capacity;   /* token slots per sequence in the cache, >= max_seq_len + D + 1 */
+    int32_t max_seq_len;   /* host-known upper bound of seq_lens[b] (sizes the launch grids) */
+} ygg_shape;
+
+/* Bytes of workspace the given operation needs for this shape (0 if the shape is invalid). */
+size_t ygg_workspace_bytes(const ygg_shape *shape, int32_t op /* ygg_op */, int32_t n_layers);
+
+/* Static, human-readable name of a status code. */
+const char *ygg_status_string(int32_t status);
+
+/*
+ * Tree-masked verify attention for one layer (paper Sec. 2 "Source of Improvements": the
+ * speculative tokens are verified in one parallel pass under a sequence-level mask; Sec. 4.2,
+ * last paragraph: the mask follows the tree's causal dependency).
+ *
+ * For every sequence b, node i and query head h (kv head g = h / (Hq/Hkv)):
+ *     keys   J(i) = cache rows 0 .. seq_lens[b]-1  U  tree rows {i, parent[i], ..., 0}
+ *     out[b,i,h,:] = sum_j softmax_j(softmax_scale * q[b,i,h,:] . k_j[g,:]) * v_j[g,:]
+ *     lse[b,i,h]   = ln sum_j exp(softmax_scale * q . k_j)            (optional)
+ * Scores, softmax and accumulation are fp32; bf16 inputs use bf16 matrix instructions with the
+ * softmax weights rounded to bf16 before the value product.
+ *
+ *   q          [B,N,Hq,Dh]      kv_dtype
+ *   k_cache    [B,cap,Hkv,Dh]   kv_dtype, rows [0,seq_lens[b]) valid, others never read
+ *   v_cache    [B,cap,Hkv,Dh]
+ *   seq_lens   [B] int32        0 <= seq_lens[b] <= max_seq_len
+ *   k_tree     [B,N,Hkv,Dh]     K/V of the tree's own tokens; must not overlap the cache
+ *   v_tree     [B,N,Hkv,Dh]
+ *   parent_idx [B,N] int32
+ *   out        [B,N,Hq,Dh]      kv_dtype (written)
+ *   lse        [B,N,Hq] fp32    written, or NULL
+ * Inputs are read-only; out/lse/workspace must not alias them.
+ */
+int32_t ygg_tree_attention(const ygg_shape *shape,
+                           const void *q, const void *k_cache, const void *v_cache,
+                           const int32_t *seq_lens, const void *k_tree, const void *v_tree,
+                           const int32_t *parent_idx, void *out, float *lse,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * One draft step d (1..D) of the Equal-Growth Tree (paper Sec. 4.2 "Draft Width Selection":
+ * exactly W_draft leaves are grown per draft step, at the positions with the largest path-wise
+ * gain, using generation probabilities as acceptance surrogates).  Candidates are the
+ * (frontier node p, token v) pairs of the previous depth, F = 1 row (the root) for d = 1 and
+ * F = W rows otherwise:
+ *     score(p,v) = cum_logprob[frontier p] + log_softmax(draft_logits[b,p,:])[v]
+ * The W best candidates (higher score first; equal scores: lower p*V+v first) become nodes
+ * 1+(d-1)W .. dW in that order: parent_idx <- frontier node, token_ids <- v, cum_logprob <-
+ * score rounded to fp32.  Scores are evaluated in fp64.
+ *
+ *   draft_logits [B,F,V] fp32    row p belongs to node 1+(d-2)W+p (node 0 for d = 1)
+ *   parent_idx, token_ids [B,N] int32 and cum_logprob [B,N] fp32: in/out; depth d-1 entries are
+ *   read, depth d entries written.  The caller initialises node 0 (parent -1, cum 0).
+ * Requires N == 1 + D*W and F*V >= W.
+ */
+int32_t ygg_equal_growth_expand(const ygg_shape *shape, int32_t d, const float *draft_logits,
+                                int32_t *parent_idx, int32_t *token_ids, float *cum_logprob,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Greedy acceptance and K/V compaction (paper Sec. 1: draft tokens that match the verifier's
+ * own output are accepted; Sec. 5: the "accept speculation management" stage; Sec. 4.1 under
+ * Eq. 2: the verifier's token after the last accepted one is the bonus token; Sec. 6: the
+ * TokenTree owns the K/V tensors).  Everything stays on the device:
+ *     t*[i]    = argmax_v target_logits[b,i,v]          (first maximum)
+ *     match[0] = 1;  match[i] = match[parent[i]] and token_ids[i] == t*[parent[i]]
+ *     best     = matched node of greatest depth (lowest index among equals)
+ *     accept_path[b,:] = root .. best, padded with -1;  accept_len[b] = depth(best)+1
+ *     bonus_token[b]   = t*[best]
+ *     for every layer: cache[layer,b,seq_lens[b]+k] = tree[layer,b,accept_path[b,k]], K and V
+ *     seq_lens[b] += accept_len[b]
+ *
+ *   target_logits [B,N,V] fp32, or NULL when target_tokens [B,N] int32 (the argmax) is given;
+ *                 exactly one of the two must be non-NULL
+ *   parent_idx, token_ids [B,N] int32
+ *   k_tree, v_tree   [n_layers,B,N,Hkv,Dh]    kv_dtype (may be NULL when n_layers == 0)
+ *   k_cache, v_cache [n_layers,B,cap,Hkv,Dh]  kv_dtype, updated in place
+ *   seq_lens [B] int32 in/out; accept_len [B], accept_path [B,D+1], bonus_token [B] int32 out
+ */
+int32_t ygg_accept_and_compact(const ygg_shape *shape, int32_t n_layers,
+                               const float *target_logits, const int32_t *target_tokens,
+                               const int32_t *parent_idx, const int32_t *token_ids,
+                               const void *k_tree, const void *v_tree,
+                               void *k_cache, void *v_cache, int32_t *seq_lens,
+                               int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* YGG_H */

@@ -1,0 +1,163 @@
+"""ctypes binding of include/ygg.h: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, checks dtypes/contiguity,
+passes raw device pointers and the current HIP stream to the C ABI, and raises on a non-zero
+status.  There is no CPU or PyTorch fallback: if libygg.so is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+OP_ATTENTION, OP_EXPAND, OP_ACCEPT = 0, 1, 2
+F32, BF16 = 0, 1
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("depth", ctypes.c_int32), ("width", ctypes.c_int32),
+        ("n_nodes", ctypes.c_int32), ("vocab", ctypes.c_int32), ("kv_dtype", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("kv_capacity", ctypes.c_int64), ("max_seq_len", ctypes.c_int32),
+    ]
+
+
+@dataclass
+class Shape:
+    """Mirror of ygg_shape (see include/ygg.h for the meaning of every field)."""
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    depth: int
+    width: int
+    n_nodes: int
+    vocab: int
+    kv_dtype: int
+    softmax_scale: float
+    kv_capacity: int
+    max_seq_len: int
+
+    def c(self) -> _CShape:
+        return _CShape(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.depth, self.width,
+                       self.n_nodes, self.vocab, self.kv_dtype, self.softmax_scale, self.kv_capacity,
+                       self.max_seq_len)
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(_PKG, "libygg.so")
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libygg.so (built by paper_2512_23858_amd/build.py).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} not found: build it with `python -m paper_2512_23858_amd.build` "
+                               "(there is no fallback path)")
+        lib = ctypes.CDLL(path)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        shp = ctypes.POINTER(_CShape)
+        lib.ygg_workspace_bytes.restype = sz
+        lib.ygg_workspace_bytes.argtypes = [shp, i32, i32]
+        lib.ygg_status_string.restype = ctypes.c_char_p
+        lib.ygg_status_string.argtypes = [i32]
+        lib.ygg_tree_attention.restype = i32
+        lib.ygg_tree_attention.argtypes = [shp] + [vp] * 9 + [vp, sz, vp]
+        lib.ygg_equal_growth_expand.restype = i32
+        lib.ygg_equal_growth_expand.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp]
+        lib.ygg_accept_and_compact.restype = i32
+        lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
+        _lib = lib
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return load_library().ygg_status_string(code).decode()
+
+
+def workspace_bytes(shape: Shape, op: int, n_layers: int = 0) -> int:
+    cs = shape.c()
+    return int(load_library().ygg_workspace_bytes(ctypes.byref(cs), op, n_layers))
+
+
+def _dev(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise RuntimeError(f"{what} failed: {status_string(rc)} (status {rc})")
+
+
+def _kv_torch_dtype(shape: Shape):
+    return torch.float32 if shape.kv_dtype == F32 else torch.bfloat16
+
+
+def _ws(workspace):
+    if workspace is None:
+        return None, 0
+    return _dev(workspace, None, "workspace"), workspace.numel() * workspace.element_size()
+
+
+def tree_attention(shape: Shape, q, k_cache, v_cache, seq_lens, k_tree, v_tree, parent_idx, out, lse=None,
+                   workspace=None):
+    """ygg_tree_attention: writes `out` (and `lse` if given) on the current stream."""
+    dt = _kv_torch_dtype(shape)
+    cs = shape.c()
+    wsp, wsn = _ws(workspace)
+    rc = load_library().ygg_tree_attention(
+        ctypes.byref(cs), _dev(q, dt, "q"), _dev(k_cache, dt, "k_cache"), _dev(v_cache, dt, "v_cache"),
+        _dev(seq_lens, torch.int32, "seq_lens"), _dev(k_tree, dt, "k_tree"), _dev(v_tree, dt, "v_tree"),
+        _dev(parent_idx, torch.int32, "parent_idx"), _dev(out, dt, "out"), _dev(lse, torch.float32, "lse"),
+        wsp, wsn, _stream())
+    _check(rc, "ygg_tree_attention")
+    return out
+
+
+def equal_growth_expand(shape: Shape, d: int, draft_logits, parent_idx, token_ids, cum_logprob, workspace=None):
+    """ygg_equal_growth_expand: fills the depth-d slots of parent_idx/token_ids/cum_logprob."""
+    cs = shape.c()
+    wsp, wsn = _ws(workspace)
+    rc = load_library().ygg_equal_growth_expand(
+        ctypes.byref(cs), d, _dev(draft_logits, torch.float32, "draft_logits"),
+        _dev(parent_idx, torch.int32, "parent_idx"), _dev(token_ids, torch.int32, "token_ids"),
+        _dev(cum_logprob, torch.float32, "cum_logprob"), wsp, wsn, _stream())
+    _check(rc, "ygg_equal_growth_expand")
+
+
+def accept_and_compact(shape: Shape, n_layers: int, parent_idx, token_ids, k_tree, v_tree, k_cache, v_cache,
+                       seq_lens, accept_len, accept_path, bonus_token, target_logits=None, target_tokens=None,
+                       workspace=None):
+    """ygg_accept_and_compact: updates the caches and seq_lens in place, fills the three outputs."""
+    dt = _kv_torch_dtype(shape)
+    cs = shape.c()
+    wsp, wsn = _ws(workspace)
+    rc = load_library().ygg_accept_and_compact(
+        ctypes.byref(cs), n_layers, _dev(target_logits, torch.float32, "target_logits"),
+        _dev(target_tokens, torch.int32, "target_tokens"), _dev(parent_idx, torch.int32, "parent_idx"),
+        _dev(token_ids, torch.int32, "token_ids"), _dev(k_tree, dt, "k_tree"), _dev(v_tree, dt, "v_tree"),
+        _dev(k_cache, dt, "k_cache"), _dev(v_cache, dt, "v_cache"), _dev(seq_lens, torch.int32, "seq_lens"),
+        _dev(accept_len, torch.int32, "accept_len"), _dev(accept_path, torch.int32, "accept_path"),
+        _dev(bonus_token, torch.int32, "bonus_token"), wsp, wsn, _stream())
+    _check(rc, "ygg_accept_and_compact")

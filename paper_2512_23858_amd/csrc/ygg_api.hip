@@ -1,0 +1,174 @@
+// Host side of the C ABI: argument validation, launch plans, workspace carving.  No device work
+// is done here other than enqueuing kernels on the caller's stream; nothing synchronises.
+#include "ygg_internal.h"
+
+namespace ygg {
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+bool common_shape_ok(const ygg_shape& s) {
+    if (s.batch < 1 || s.batch > 65535) return false;
+    if (s.n_q_heads < 1 || s.n_kv_heads < 1 || s.n_q_heads % s.n_kv_heads != 0) return false;
+    if (s.depth < 0 || s.width < 1 || s.n_nodes < 1) return false;
+    if (s.max_seq_len < 0 || s.kv_capacity < (int64_t)s.max_seq_len + s.depth + 1) return false;
+    return true;
+}
+
+int32_t check_shape(const ygg_shape* s, bool need_kv, bool need_vocab) {
+    if (!s) return YGG_ERR_NULL;
+    if (!common_shape_ok(*s)) return YGG_ERR_SHAPE;
+    if (s->n_nodes > kMaxNodes || s->width > kMaxWidth) return YGG_ERR_UNSUPPORTED;
+    if (need_kv) {
+        if (s->kv_dtype != YGG_F32 && s->kv_dtype != YGG_BF16) return YGG_ERR_UNSUPPORTED;
+        if (s->head_dim != 64 && s->head_dim != 128) return YGG_ERR_UNSUPPORTED;
+    }
+    if (need_vocab && s->vocab < 1) return YGG_ERR_SHAPE;
+    return YGG_OK;
+}
+
+int32_t check_workspace(const void* ws, size_t have, size_t need) {
+    if (need == 0) return YGG_OK;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || have < need) return YGG_ERR_WORKSPACE;
+    return YGG_OK;
+}
+
+}  // namespace
+
+AttnPlan plan_attention(const ygg_shape& s) {
+    AttnPlan p{};
+    const int64_t rows = (int64_t)s.batch * s.n_nodes * s.n_q_heads;
+    const int64_t T = (int64_t)s.max_seq_len + s.n_nodes;
+    const int64_t max_split = (T + kKeyTile - 1) / kKeyTile;
+    p.use_mfma = 0;
+    // vector path: one wavefront per (row, split); aim for ~4096 wavefronts
+    int64_t ns = (4096 + rows - 1) / rows;
+    if (ns > max_split) ns = max_split;
+    if (ns < 1) ns = 1;
+    if (ns > 64) ns = 64;
+    p.nsplit = (int32_t)ns;
+    p.part_o_bytes = align256((size_t)p.nsplit * (size_t)rows * (size_t)s.head_dim * sizeof(float));
+    p.part_ml_bytes = align256((size_t)p.nsplit * (size_t)rows * 2 * sizeof(float));
+    return p;
+}
+
+hipError_t launch_attn_mfma(const AttnArgs&, const AttnPlan&, hipStream_t) { return hipErrorNotSupported; }
+
+}  // namespace ygg
+
+using namespace ygg;
+
+extern "C" {
+
+const char* ygg_status_string(int32_t status) {
+    switch (status) {
+        case YGG_OK: return "ok";
+        case YGG_ERR_NULL: return "null pointer";
+        case YGG_ERR_SHAPE: return "inconsistent shape";
+        case YGG_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or size";
+        case YGG_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case YGG_ERR_LAUNCH: return "kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+size_t ygg_workspace_bytes(const ygg_shape* s, int32_t op, int32_t n_layers) {
+    (void)n_layers;
+    if (!s) return 0;
+    switch (op) {
+        case YGG_OP_ATTENTION: {
+            if (check_shape(s, true, false) != YGG_OK) return 0;
+            const AttnPlan p = plan_attention(*s);
+            return p.part_o_bytes + p.part_ml_bytes;
+        }
+        case YGG_OP_EXPAND: {
+            if (check_shape(s, false, true) != YGG_OK) return 0;
+            const ExpandPlan p = plan_expand(*s, 2);  // the widest frontier
+            return p.stat_bytes + p.cand_bytes;
+        }
+        case YGG_OP_ACCEPT: {
+            if (check_shape(s, false, true) != YGG_OK) return 0;
+            const AcceptPlan p = plan_accept(*s);
+            return p.part_bytes + p.oldlen_bytes;
+        }
+        default: return 0;
+    }
+}
+
+int32_t ygg_tree_attention(const ygg_shape* s, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* seq_lens, const void* k_tree, const void* v_tree,
+                           const int32_t* parent_idx, void* out, float* lse, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    if (int32_t rc = check_shape(s, true, false)) return rc;
+    if (!q || !k_tree || !v_tree || !seq_lens || !parent_idx || !out) return YGG_ERR_NULL;
+    if (s->max_seq_len > 0 && (!k_cache || !v_cache)) return YGG_ERR_NULL;
+    const AttnPlan p = plan_attention(*s);
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes)) return rc;
+
+    AttnArgs a{};
+    a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
+    a.seq_lens = seq_lens; a.parent_idx = parent_idx;
+    a.part_o = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.part_o_bytes);
+    a.out = out; a.lse = lse;
+    a.B = s->batch; a.N = s->n_nodes; a.Hq = s->n_q_heads; a.Hkv = s->n_kv_heads;
+    a.G = s->n_q_heads / s->n_kv_heads; a.Dh = s->head_dim;
+    a.nsplit = p.nsplit; a.max_seq_len = s->max_seq_len; a.cap = s->kv_capacity; a.scale = s->softmax_scale;
+
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = p.use_mfma ? launch_attn_mfma(a, p, st) : launch_attn_vector(a, p, s->kv_dtype, st);
+    if (e != hipSuccess) return YGG_ERR_LAUNCH;
+    e = launch_attn_combine(a, p, s->kv_dtype, st);
+    return e == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
+int32_t ygg_equal_growth_expand(const ygg_shape* s, int32_t d, const float* draft_logits, int32_t* parent_idx,
+                                int32_t* token_ids, float* cum_logprob, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+    if (int32_t rc = check_shape(s, false, true)) return rc;
+    if (!draft_logits || !parent_idx || !token_ids || !cum_logprob) return YGG_ERR_NULL;
+    if (s->depth < 1 || d < 1 || d > s->depth) return YGG_ERR_SHAPE;
+    if ((int64_t)s->n_nodes != 1 + (int64_t)s->depth * s->width) return YGG_ERR_SHAPE;
+    const ExpandPlan p = plan_expand(*s, d);
+    if ((int64_t)p.F * s->vocab < s->width) return YGG_ERR_SHAPE;
+    if ((int64_t)p.F * p.nchunk > 4096) return YGG_ERR_UNSUPPORTED;  // merge holds <= 16 lists per thread
+    if ((int64_t)s->batch * p.F > 0x7fffffffLL || p.nchunk > 65535) return YGG_ERR_UNSUPPORTED;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.stat_bytes + p.cand_bytes)) return rc;
+
+    ExpandArgs a{};
+    a.logits = draft_logits; a.parent_idx = parent_idx; a.token_ids = token_ids; a.cum_logprob = cum_logprob;
+    a.stats = workspace;
+    a.cands = static_cast<char*>(workspace) + p.stat_bytes;
+    a.B = s->batch; a.D = s->depth; a.W = s->width; a.V = s->vocab; a.N = s->n_nodes; a.d = d;
+    a.F = p.F; a.chunk = p.chunk; a.nchunk = p.nchunk;
+    return launch_expand(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
+int32_t ygg_accept_and_compact(const ygg_shape* s, int32_t n_layers, const float* target_logits,
+                               const int32_t* target_tokens, const int32_t* parent_idx, const int32_t* token_ids,
+                               const void* k_tree, const void* v_tree, void* k_cache, void* v_cache,
+                               int32_t* seq_lens, int32_t* accept_len, int32_t* accept_path, int32_t* bonus_token,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (int32_t rc = check_shape(s, n_layers > 0, target_logits != nullptr)) return rc;
+    if (n_layers < 0 || n_layers > 65535) return YGG_ERR_SHAPE;
+    if ((target_logits == nullptr) == (target_tokens == nullptr)) return YGG_ERR_NULL;
+    if (!parent_idx || !token_ids || !seq_lens || !accept_len || !accept_path || !bonus_token) return YGG_ERR_NULL;
+    if (n_layers > 0 && (!k_tree || !v_tree || !k_cache || !v_cache)) return YGG_ERR_NULL;
+    const AcceptPlan p = plan_accept(*s);
+    if ((int64_t)s->batch * s->n_nodes > 0x7fffffffLL || p.nchunk > 65535) return YGG_ERR_UNSUPPORTED;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_bytes + p.oldlen_bytes)) return rc;
+
+    AcceptArgs a{};
+    a.target_logits = target_logits; a.target_tokens = target_tokens;
+    a.parent_idx = parent_idx; a.token_ids = token_ids;
+    a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_cache; a.v_cache = v_cache;
+    a.seq_lens = seq_lens; a.accept_len = accept_len; a.accept_path = accept_path; a.bonus_token = bonus_token;
+    a.part = workspace;
+    a.old_len = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + p.part_bytes);
+    a.B = s->batch; a.N = s->n_nodes; a.D = s->depth; a.V = s->vocab; a.Hkv = s->n_kv_heads; a.Dh = s->head_dim;
+    a.n_layers = n_layers; a.chunk = p.chunk; a.nchunk = p.nchunk; a.max_seq_len = s->max_seq_len;
+    a.elem_bytes = s->kv_dtype == YGG_F32 ? 4 : 2; a.cap = s->kv_capacity;
+    return launch_accept(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
+}  // extern "C"

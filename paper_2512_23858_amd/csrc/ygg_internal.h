@@ -1,0 +1,98 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ygg.h"
+
+namespace ygg {
+
+constexpr int kMaxNodes = 1024;      // N limit (ancestor bitmasks and per-tree tables live in LDS)
+constexpr int kMaxWidth = 64;        // W limit (one wavefront holds a candidate list)
+constexpr int kKeyTile = 64;         // split boundaries of the key range are multiples of this
+
+// ---- tree attention ---------------------------------------------------------------------------
+// Key index space of sequence b: [0, L_b) are cache rows, [L_b, L_b + N) are the tree's own rows.
+// Split s of nsplit covers [s*chunk, min((s+1)*chunk, L_b+N)), chunk = ceil((L_b+N)/nsplit)
+// rounded up to kKeyTile.  Every split writes an un-normalised partial (m, l, O~) per query row.
+struct AttnArgs {
+    const void* q;
+    const void* k_cache;
+    const void* v_cache;
+    const void* k_tree;
+    const void* v_tree;
+    const int32_t* seq_lens;
+    const int32_t* parent_idx;
+    float* part_o;    // [nsplit][B*N*Hq][Dh]
+    float* part_ml;   // [nsplit][B*N*Hq][2]   (running max m in scaled-score units, sum l)
+    void* out;
+    float* lse;
+    int32_t B, N, Hq, Hkv, G, Dh;
+    int32_t nsplit, max_seq_len;
+    int64_t cap;
+    float scale;
+};
+
+struct AttnPlan {
+    int32_t nsplit;
+    int32_t use_mfma;       // 1: bf16 matrix-core kernel, 0: fp32 vector kernel
+    int32_t waves;          // MFMA kernel: wavefronts per workgroup
+    int32_t rblocks;        // MFMA kernel: 32-row blocks per wavefront
+    int32_t row_tiles;      // MFMA kernel: workgroups along the N*G query rows of one kv head
+    size_t part_o_bytes, part_ml_bytes;
+};
+
+AttnPlan plan_attention(const ygg_shape& s);
+hipError_t launch_attn_vector(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
+hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st);
+hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
+
+// ---- equal-growth expansion -------------------------------------------------------------------
+struct ExpandPlan {
+    int32_t F;            // frontier rows
+    int32_t chunk;        // vocab entries per scan workgroup
+    int32_t nchunk;
+    size_t stat_bytes;    // [B*F][nchunk] {double sumexp; float max; int32 count}
+    size_t cand_bytes;    // [B*F][nchunk][W] {float val; int32 idx}
+};
+struct ExpandArgs {
+    const float* logits;
+    int32_t* parent_idx;
+    int32_t* token_ids;
+    float* cum_logprob;
+    void* stats;
+    void* cands;
+    int32_t B, D, W, V, N, d, F, chunk, nchunk;
+};
+ExpandPlan plan_expand(const ygg_shape& s, int32_t d);
+hipError_t launch_expand(const ExpandArgs& a, hipStream_t st);
+
+// ---- acceptance + compaction ------------------------------------------------------------------
+struct AcceptPlan {
+    int32_t chunk, nchunk;
+    size_t part_bytes;    // [B*N][nchunk] {float val; int32 idx}
+    size_t oldlen_bytes;  // [B] int32: sequence lengths before the update
+};
+struct AcceptArgs {
+    const float* target_logits;
+    const int32_t* target_tokens;
+    const int32_t* parent_idx;
+    const int32_t* token_ids;
+    const void* k_tree;
+    const void* v_tree;
+    void* k_cache;
+    void* v_cache;
+    int32_t* seq_lens;
+    int32_t* accept_len;
+    int32_t* accept_path;
+    int32_t* bonus_token;
+    void* part;
+    int32_t* old_len;
+    int32_t B, N, D, V, Hkv, Dh, n_layers, chunk, nchunk, max_seq_len;
+    int32_t elem_bytes;
+    int64_t cap;
+};
+AcceptPlan plan_accept(const ygg_shape& s);
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t st);
+
+}  // namespace ygg
