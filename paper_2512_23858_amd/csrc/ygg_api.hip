@@ -39,20 +39,46 @@ AttnPlan plan_attention(const ygg_shape& s) {
     AttnPlan p{};
     const int64_t rows = (int64_t)s.batch * s.n_nodes * s.n_q_heads;
     const int64_t T = (int64_t)s.max_seq_len + s.n_nodes;
-    const int64_t max_split = (T + kKeyTile - 1) / kKeyTile;
-    p.use_mfma = 0;
-    // vector path: one wavefront per (row, split); aim for ~4096 wavefronts
-    int64_t ns = (4096 + rows - 1) / rows;
-    if (ns > max_split) ns = max_split;
+    const int64_t tiles = (T + kKeyTile - 1) / kKeyTile;
+    int64_t ns;
+    p.use_mfma = s.kv_dtype == YGG_BF16 && s.head_dim == 128;
+    if (p.use_mfma) {
+        // query rows that share one K/V stream, and the workgroup shape that wastes the fewest of them
+        const int R = s.n_nodes * (s.n_q_heads / s.n_kv_heads);
+        if (R <= 32) { p.waves = 1; p.rblocks = 1; }
+        else if (R <= 64) { p.waves = 2; p.rblocks = 1; }
+        else if (R <= 128) { p.waves = 4; p.rblocks = 1; }
+        else {
+            const int cand[3][2] = {{4, 2}, {3, 2}, {2, 2}};
+            int best_pad = 0x7fffffff;
+            for (const auto& c : cand) {
+                const int rw = c[0] * c[1] * 32;
+                const int pad = (R + rw - 1) / rw * rw;
+                if (pad < best_pad) { best_pad = pad; p.waves = c[0]; p.rblocks = c[1]; }
+            }
+        }
+        const int rw = p.waves * p.rblocks * 32;
+        p.row_tiles = (R + rw - 1) / rw;
+        // about two rounds of workgroups over the 256 CUs, at least two key tiles per split
+        const int64_t per_split = (int64_t)s.batch * s.n_kv_heads * p.row_tiles;
+        const int64_t target = 512 * (p.rblocks == 2 ? 1 : 2);
+        ns = target / per_split;
+        if (ns > tiles / 2) ns = tiles / 2;
+    } else {
+        // vector path: one wavefront per (row, split); aim for ~4096 wavefronts
+        ns = (4096 + rows - 1) / rows;
+        if (ns > tiles) ns = tiles;
+    }
     if (ns < 1) ns = 1;
     if (ns > 64) ns = 64;
+    // drop the splits that rounding the chunk to whole key tiles leaves empty
+    const int64_t chunk = ((T + ns - 1) / ns + kKeyTile - 1) / kKeyTile * kKeyTile;
+    ns = (T + chunk - 1) / chunk;
     p.nsplit = (int32_t)ns;
     p.part_o_bytes = align256((size_t)p.nsplit * (size_t)rows * (size_t)s.head_dim * sizeof(float));
     p.part_ml_bytes = align256((size_t)p.nsplit * (size_t)rows * 2 * sizeof(float));
     return p;
 }
-
-hipError_t launch_attn_mfma(const AttnArgs&, const AttnPlan&, hipStream_t) { return hipErrorNotSupported; }
 
 }  // namespace ygg
 
@@ -118,6 +144,7 @@ int32_t ygg_tree_attention(const ygg_shape* s, const void* q, const void* k_cach
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     hipError_t e = p.use_mfma ? launch_attn_mfma(a, p, st) : launch_attn_vector(a, p, s->kv_dtype, st);
     if (e != hipSuccess) return YGG_ERR_LAUNCH;
+    if (p.use_mfma && p.nsplit == 1) return YGG_OK;  // the kernel wrote the final rows itself
     e = launch_attn_combine(a, p, s->kv_dtype, st);
     return e == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
 }

@@ -1,0 +1,105 @@
+"""GPU parity of tree attention against the CPU oracle, through the C ABI.
+
+bf16 cases: the contractual bound (2e-2 max-abs, 1e-2 mean-abs) cannot see a wrong ancestor mask
+on N(0,1) inputs, so every case also has to pass two tighter gates: error relative to the
+oracle's RMS <= 2 % and LSE within 1e-3; the short-prefix and tree-heavy cases make the tree keys
+carry most of the softmax mass.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import ygg_workloads as wl
+from gpu_util import run_attention, shape_of
+
+pytestmark = pytest.mark.gpu
+
+
+def _cfg(B, Hq, Hkv, D, W, dtype="bf16", Dh=128, seed=77):
+    return wl.Config("case", B, Hq, Hkv, Dh, dtype, 0, (), D, W, 100, (0.5,), "dirichlet", 0.5, 1, seed)
+
+
+def _inputs(cfg, lens, max_len, parent=None, tree_gain=1.0):
+    lens = np.asarray(lens, np.int32)
+    cfg = wl.scaled(cfg, prefix_len=int(max_len))
+    host = wl.attention_inputs(cfg, lens=lens)
+    if parent is None:
+        parent = wl.trees(cfg)
+    if tree_gain != 1.0:   # make the tree's own keys dominate the softmax
+        k = wl.storage_to_f64(host["k_tree"]) * tree_gain
+        host["k_tree"] = wl.to_storage(k.astype(np.float32), cfg.dtype)
+    return cfg, host, parent
+
+
+def _check(cfg, host, parent, max_len, n_nodes=None, depth=None):
+    ref_out, ref_lse = oracle.tree_attention(host["q"], host["k_cache"], host["v_cache"], host["seq_lens"],
+                                             host["k_tree"], host["v_tree"], parent, cfg.softmax_scale)
+    shape = shape_of(cfg, max_seq_len=int(max_len), n_nodes=n_nodes)
+    if depth is not None:
+        shape.depth = depth
+        shape.kv_capacity = max(shape.kv_capacity, int(max_len) + depth + 1)
+    out, lse = run_attention(shape, host, parent)
+    err = np.abs(out - ref_out)
+    if cfg.dtype == "f32":
+        assert err.max() <= 1e-5, err.max()
+        assert np.abs(lse - ref_lse).max() <= 1e-5
+    else:
+        assert err.max() <= 2e-2 and err.mean() <= 1e-2, (err.max(), err.mean())
+        rms = np.sqrt((ref_out ** 2).mean())
+        assert np.sqrt((err ** 2).mean()) <= 0.02 * rms, (np.sqrt((err ** 2).mean()), rms)
+        assert np.abs(lse - ref_lse).max() <= 1e-3, np.abs(lse - ref_lse).max()
+
+
+# (B, Hq, Hkv, D, W, lens, max_len): query rows per kv head R = (1+D*W)*Hq/Hkv select the workgroup shape
+BF16_CASES = [
+    (1, 4, 4, 3, 4, [128], 128),            # R = 13, one key split
+    (2, 8, 8, 6, 8, [300, 1], 300),         # R = 49, ragged batch
+    (1, 8, 2, 4, 6, [130], 130),            # R = 100
+    (2, 8, 2, 8, 4, [200, 77], 333),        # R = 132, max_seq_len above every length
+    (1, 16, 2, 5, 6, [257], 257),           # R = 248
+    (1, 8, 2, 10, 9, [65], 65),             # R = 364
+    (1, 4, 1, 10, 15, [190], 190),          # R = 604
+    (1, 8, 8, 6, 8, [1500], 1500),          # several key splits, partial last tile
+    (3, 8, 2, 3, 4, [700, 0, 64], 700),     # several splits with an empty and a one-tile sequence
+]
+
+
+@pytest.mark.parametrize("case", BF16_CASES, ids=lambda c: f"B{c[0]}_Hq{c[1]}_Hkv{c[2]}_D{c[3]}W{c[4]}_L{max(c[5])}")
+def test_bf16_shapes(case):
+    B, Hq, Hkv, D, W, lens, max_len = case
+    cfg, host, parent = _inputs(_cfg(B, Hq, Hkv, D, W), lens, max_len)
+    _check(cfg, host, parent, max_len)
+
+
+@pytest.mark.parametrize("L", [0, 1, 31, 32, 33, 63, 64, 65])
+@pytest.mark.parametrize("gain", [1.0, 4.0])
+def test_bf16_short_prefix_and_tree_heavy(L, gain):
+    cfg, host, parent = _inputs(_cfg(1, 8, 2, 5, 7, seed=91), [L], max(L, 1), tree_gain=gain)
+    _check(cfg, host, parent, max(L, 1))
+
+
+def test_bf16_chain_and_general_tree():
+    N = 45
+    for parent in (wl.chain_tree(N)[None], wl.random_topological_tree(5, N)[None]):
+        cfg, host, _ = _inputs(_cfg(1, 8, 4, 4, 11, seed=92), [150], 150, parent=parent, tree_gain=3.0)
+        _check(cfg, host, parent, 150, depth=N - 1)
+
+
+def test_bf16_single_node_tree():
+    cfg = wl.Config("decode", 2, 8, 2, 128, "bf16", 0, (), 0, 1, 100, (0.5,), "uniform", 0.0, 1, 93)
+    cfg, host, parent = _inputs(cfg, [100, 259], 259)
+    _check(cfg, host, parent, 259)
+
+
+@pytest.mark.parametrize("case", [(1, 4, 4, 3, 4, [128], 128, 64), (2, 8, 2, 4, 6, [200, 77], 200, 128),
+                                  (1, 8, 8, 6, 8, [1500], 1500, 128), (1, 4, 2, 5, 7, [0], 1, 64)],
+                         ids=["tiny", "gqa_ragged", "splits", "empty_prefix"])
+def test_fp32_shapes(case):
+    B, Hq, Hkv, D, W, lens, max_len, Dh = case
+    cfg, host, parent = _inputs(_cfg(B, Hq, Hkv, D, W, dtype="f32", Dh=Dh, seed=94), lens, max_len)
+    _check(cfg, host, parent, max_len)
+
+
+def test_bf16_head_dim_64_uses_vector_path():
+    cfg, host, parent = _inputs(_cfg(1, 4, 2, 3, 4, Dh=64, seed=95), [90], 90)
+    _check(cfg, host, parent, 90)
