@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input:
+  D calls of ygg_equal_growth_expand, n_layers calls of ygg_tree_attention (one per layer, each
+  layer with its own Q/K/V buffers), one call of ygg_accept_and_compact over all layers.
+Inputs are seeded, synthetic and already resident in HBM when the timed region starts.
+
+Prints ONE JSON line: the verify-step time per layer (whole step / n_layers), the roofline of the
+dominant kernel (tree attention, timed with dispatch-bound HIP events on its own stream) and the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def attention_work(cfg, lens):
+    """Algorithmic bytes and flops of one tree-attention layer."""
+    e = 4 if cfg.dtype == "f32" else 2
+    N, Hq, Hkv, Dh, B = cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.batch
+    sumL = int(np.sum(lens))
+    nbytes = 2 * sumL * Hkv * Dh * e + 2 * B * N * Hkv * Dh * e + 2 * B * N * Hq * Dh * e
+    flops = 4 * N * Hq * Dh * (sumL + B * N)
+    return nbytes, flops
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attention-only", action="store_true", help="time only the attention calls of a step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); sharding is described in DESIGN.md",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_23858_amd as ygg
+    import ygg_workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    ygg.load_library()  # fails loudly if libygg.so is missing
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[args.config]
+    n_layers = args.layers or cfg.n_layers
+    B, N, D, W, V = cfg.batch, cfg.n_nodes, cfg.depth, cfg.width, cfg.vocab
+    Hkv, Dh, cap = cfg.n_kv_heads, cfg.head_dim, cfg.kv_capacity
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+
+    def up(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    # ---------------- inputs (host generator, then resident in HBM)
+    lens_h = wl.seq_lens(cfg)
+    parent_h = wl.trees(cfg)
+    token_h = wl.tokens(cfg, parent_h)
+    q = torch.empty((n_layers, B, N, cfg.n_q_heads, Dh), dtype=tdt, device=dev)
+    k_cache = torch.empty((n_layers, B, cap, Hkv, Dh), dtype=tdt, device=dev)
+    v_cache = torch.empty_like(k_cache)
+    k_tree = torch.empty((n_layers, B, N, Hkv, Dh), dtype=tdt, device=dev)
+    v_tree = torch.empty_like(k_tree)
+    layer0 = None
+    for layer in range(n_layers):
+        h = wl.attention_inputs(cfg, layer=layer, lens=lens_h)
+        if layer == 0:
+            layer0 = h
+        q[layer], k_cache[layer], v_cache[layer] = up(h["q"]), up(h["k_cache"]), up(h["v_cache"])
+        k_tree[layer], v_tree[layer] = up(h["k_tree"]), up(h["v_tree"])
+    out = torch.empty_like(q)
+    draft_h = [wl.expansion_inputs(cfg, d) for d in range(1, D + 1)]
+    draft = [up(x) for x in draft_h]
+    target_h = wl.acceptance_inputs(cfg, parent_h, token_h)
+    target = up(target_h)
+    parent, token = up(parent_h), up(token_h)
+    lens0 = up(lens_h)
+    lens = lens0.clone()
+    e_parent = torch.full((B, N), -1, dtype=torch.int32, device=dev)
+    e_token = torch.zeros((B, N), dtype=torch.int32, device=dev)
+    e_cum = torch.zeros((B, N), dtype=torch.float32, device=dev)
+    accept_len = torch.zeros((B,), dtype=torch.int32, device=dev)
+    accept_path = torch.zeros((B, D + 1), dtype=torch.int32, device=dev)
+    bonus = torch.zeros((B,), dtype=torch.int32, device=dev)
+
+    shape = ygg.Shape(batch=B, n_q_heads=cfg.n_q_heads, n_kv_heads=Hkv, head_dim=Dh, depth=D, width=W, n_nodes=N,
+                      vocab=V, kv_dtype=0 if cfg.dtype == "f32" else 1, softmax_scale=cfg.softmax_scale,
+                      kv_capacity=cap, max_seq_len=cfg.max_prefix)
+    ws = [torch.empty(max(ygg.workspace_bytes(shape, op, n_layers), 256), dtype=torch.uint8, device=dev)
+          for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT)]
+
+    def attention_pass():
+        for layer in range(n_layers):
+            ygg.tree_attention(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer], v_tree[layer],
+                               parent, out[layer], None, ws[0])
+
+    def step():
+        lens.copy_(lens0)   # acceptance advances seq_lens; every step starts from the same state
+        for d in range(1, D + 1):
+            ygg.equal_growth_expand(shape, d, draft[d - 1], e_parent, e_token, e_cum, ws[1])
+        attention_pass()
+        ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
+                               accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
+
+    body = attention_pass if args.attention_only else step
+    for _ in range(args.warmup):
+        body()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(args.steps):
+        body()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+
+    # ---------------- dominant kernel: same launches again with dispatch-bound events
+    ygg.profile_begin(args.steps * n_layers)
+    for _ in range(args.steps):
+        body()
+    kern_us, kern_n = ygg.profile_end()
+    nbytes, flops = attention_work(cfg, lens_h)
+    t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+    if cfg.dtype == "f32":
+        bound, peak, unit, ach = "alu", FP32_VALU_PEAK_TFLOPS, "TFLOP/s", flops / (kern_us * 1e-6) / 1e12
+    elif flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > t_hbm:
+        bound, peak, unit, ach = "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", flops / (kern_us * 1e-6) / 1e12
+    else:
+        bound, peak, unit, ach = "hbm", HBM_PEAK_GBS, "GB/s", nbytes / (kern_us * 1e-6) / 1e9
+    roofline = {"bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
+                "traffic": None, "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
+                "launches_timed": kern_n, "algorithmic_bytes": nbytes, "flops": flops,
+                "gbps": round(nbytes / (kern_us * 1e-6) / 1e9, 1), "tflops": round(flops / (kern_us * 1e-6) / 1e12, 2)}
+
+    # ---------------- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        rows_all = B * N * cfg.n_q_heads
+        # attention: time a sample of output rows of layer 0 sized for roughly 10 s, scale to all rows and layers
+        t = time.perf_counter()
+        probe = min(rows_all, 4 * threads)
+        rs = np.random.default_rng(0).choice(rows_all, size=probe, replace=False)
+        def run_rows(sel):
+            # the oracle's full routine parallelises over rows; sampled rows go through the row routine
+            for r in sel:
+                b_, i_, h_ = r // (N * cfg.n_q_heads), (r // cfg.n_q_heads) % N, r % cfg.n_q_heads
+                oracle.attention_row(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                     layer0["v_tree"], parent_h, cfg.softmax_scale, int(b_), int(i_), int(h_))
+        run_rows(rs)
+        per_row_serial = (time.perf_counter() - t) / probe
+        est_full = per_row_serial * rows_all / threads
+        if est_full <= 20.0:
+            t = time.perf_counter()
+            oracle.tree_attention(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                  layer0["v_tree"], parent_h, cfg.softmax_scale)
+            t_attn_layer = time.perf_counter() - t
+            attn_note = "attention: all rows of layer 0 (OpenMP over rows)"
+        else:
+            t_attn_layer = est_full
+            attn_note = (f"attention: {probe} sampled rows of layer 0 run serially, scaled to {rows_all} rows "
+                         f"and {threads} threads")
+        # expansion: all D steps; acceptance: argmax + match + compaction of one layer
+        p2 = np.full((B, N), -1, np.int32); t2 = np.zeros((B, N), np.int32); c2 = np.zeros((B, N), np.float32)
+        t = time.perf_counter()
+        for d in range(1, D + 1):
+            oracle.expand(D, W, d, draft_h[d - 1], p2, t2, c2)
+        t_expand = time.perf_counter() - t
+        kt1 = np.ascontiguousarray(layer0["k_tree"][None]); vt1 = np.ascontiguousarray(layer0["v_tree"][None])
+        kc1 = np.ascontiguousarray(layer0["k_cache"][None]); vc1 = np.ascontiguousarray(layer0["v_cache"][None])
+        t = time.perf_counter()
+        oracle.accept_compact(D + 1, parent_h, token_h, kt1, vt1, kc1, vc1, lens_h.copy(), target_logits=target_h)
+        t_accept = time.perf_counter() - t
+        if args.attention_only:
+            cpu_step = n_layers * t_attn_layer
+        else:
+            cpu_step = t_expand + n_layers * t_attn_layer + t_accept
+        cpu = {"value": round(cpu_step / n_layers * 1e6, 1), "unit": "us/layer", "cores": threads, "kind": "oracle",
+               "sample": f"{attn_note}; expansion: all {D} steps; acceptance: argmax+match+1-layer compaction; "
+                         f"step = expand + {n_layers} x attention layer + accept",
+               "attention_layer_s": round(t_attn_layer, 4), "expand_s": round(t_expand, 4),
+               "accept_s": round(t_accept, 4)}
+
+    rec = {
+        "metric": "verify-step us per layer (expand + tree attention + accept/compact, whole step / layers)",
+        "value": round(ms_per_step * 1e3 / n_layers, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}] {cfg.name}", "batch": B, "q_heads": cfg.n_q_heads,
+                   "kv_heads": Hkv, "head_dim": Dh, "prefix": cfg.prefix_len or list(cfg.prefix_range),
+                   "tree": f"depth {D} x width {W} + root = {N} nodes", "vocab": V, "layers": n_layers,
+                   "scope": "attention only" if args.attention_only else "full step"},
+        "wall_ms_timed_region": round(wall_ms, 2),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -151,6 +151,18 @@ int32_t ygg_accept_and_compact(const ygg_shape *shape, int32_t n_layers,
                                int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Measurement hook for benchmarks (not part of the verification path; not thread-safe).
+ * Between ygg_profile_begin and ygg_profile_end every launch of the tree-attention main kernel
+ * is bracketed by a pair of HIP events bound to that dispatch (hipExtLaunchKernelGGL), so the
+ * elapsed time of a pair is the kernel's own execution time on the stream it ran on, without
+ * launch gaps.  ygg_profile_end synchronises the device, writes the average duration in
+ * microseconds and the number of launches seen (launches beyond max_launches are not timed),
+ * and releases the events.  Only host-side event objects are created; no device memory.
+ */
+int32_t ygg_profile_begin(int32_t max_launches);
+int32_t ygg_profile_end(double *avg_us, int32_t *n_launches);
+
 #ifdef __cplusplus
 }
 #endif

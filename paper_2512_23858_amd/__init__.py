@@ -10,6 +10,8 @@ from .binding import (  # noqa: F401
     equal_growth_expand,
     lib_path,
     load_library,
+    profile_begin,
+    profile_end,
     status_string,
     tree_attention,
     workspace_bytes,

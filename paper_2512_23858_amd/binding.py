@@ -76,6 +76,10 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_equal_growth_expand.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp]
         lib.ygg_accept_and_compact.restype = i32
         lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
+        lib.ygg_profile_begin.restype = i32
+        lib.ygg_profile_begin.argtypes = [i32]
+        lib.ygg_profile_end.restype = i32
+        lib.ygg_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         _lib = lib
     return _lib
 
@@ -161,3 +165,15 @@ def accept_and_compact(shape: Shape, n_layers: int, parent_idx, token_ids, k_tre
         _dev(accept_len, torch.int32, "accept_len"), _dev(accept_path, torch.int32, "accept_path"),
         _dev(bonus_token, torch.int32, "bonus_token"), wsp, wsn, _stream())
     _check(rc, "ygg_accept_and_compact")
+
+
+def profile_begin(max_launches: int):
+    """Measurement hook: time every attention main-kernel launch until profile_end()."""
+    _check(load_library().ygg_profile_begin(max_launches), "ygg_profile_begin")
+
+
+def profile_end():
+    """Returns (average kernel duration in microseconds, number of launches timed)."""
+    avg, n = ctypes.c_double(0.0), ctypes.c_int32(0)
+    _check(load_library().ygg_profile_end(ctypes.byref(avg), ctypes.byref(n)), "ygg_profile_end")
+    return avg.value, n.value

@@ -20,23 +20,66 @@
 // bitmasks built in LDS from parent_idx.
 #include "ygg_internal.h"
 
+#include <hip/hip_ext.h>
+
+#include <cstdlib>
+#include <type_traits>
+
 namespace ygg {
 namespace {
+
+// Debug builds (-DYGG_TRACE) record shader-clock stamps of workgroup 0 into a buffer whose address
+// comes from the environment; release builds compile the macro away.
+#ifdef YGG_ABLATE  // timing experiments only: 1 no tile refills, 2 no softmax, 4 no MFMA, 8 no barriers
+#define ABL(bit) ((YGG_ABLATE) & (bit))
+#else
+#define ABL(bit) 0
+#endif
+#ifdef YGG_TRACE
+__device__ long long* g_trace = nullptr;
+#define TR(tag)                                                                                   \
+    do {                                                                                          \
+        if (blockIdx.x == 0 && lane == 0 && tr_n < 250 && g_trace) {                              \
+            g_trace[(wave * 256 + tr_n) * 2] = (tag);                                             \
+            g_trace[(wave * 256 + tr_n) * 2 + 1] = __builtin_readcyclecounter();                  \
+            ++tr_n;                                                                               \
+        }                                                                                         \
+    } while (0)
+#else
+#define TR(tag) do {} while (0)
+#endif
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((ext_vector_type(8))) short i16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int DH = 128;
-constexpr int KS = 272;  // bytes between K rows in LDS (256 + 16: conflict-free 16-byte column reads)
-constexpr int VS = 288;  // bytes between V rows in LDS (256 + 32: transpose reads of 4 rows x 32 bytes)
+constexpr int ROWB = 256;  // bytes of one K or V row (head_dim 128, bf16) = 16 slots of 16 bytes
+// LDS tiles are filled by direct-to-LDS loads (64 lanes x 16 bytes land contiguously), so rows are
+// unpadded and bank conflicts are avoided by permuting the 16-byte slots inside each row instead:
+//   K tile: slot' = slot ^ (row & 15)         16 consecutive rows read the same column conflict-free
+//   V tile: slot' = slot ^ ((row & 7) << 1)   transpose reads touch 4..8 rows x 32 bytes
+// The permutation is applied on the global side (which 16 bytes a lane fetches), never in LDS.
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kRescaleGap = 8.f;  // log2 units by which a row maximum may outgrow its softmax reference
 
 __device__ __forceinline__ i16x4 lds_read_tr16(const unsigned char* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p));
 }
+
+// Direct-to-LDS load of 16 bytes per lane: lane l's data lands at LDS byte address lds_base + 16*l
+// (lds_base is wave-uniform and goes through M0).  Written as inline assembly so that the compiler
+// does not treat every later LDS read as dependent on it (it would wait for the whole prefetch
+// before each operand read); completion is awaited explicitly with dma_wait() before the barrier
+// that publishes the tile.  The compiler keeps nothing live in M0 on this target.
+__device__ __forceinline__ void dma_load16(const void* base /* wave-uniform */, uint32_t byte_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(byte_off), "s"(base) : "memory");
+}
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     // round-to-nearest-even on both halves
@@ -47,17 +90,26 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 template <int NW, int RB, int KT>
-__global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
+__global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
     constexpr int THREADS = NW * 64;
     constexpr int RW = NW * RB * 32;                             // query rows per workgroup
-    constexpr int PIECES = (KT * 16 + THREADS - 1) / THREADS;    // 16-byte pieces per thread per tile
+    constexpr int TILEB = KT * ROWB;                             // bytes of one K (or V) tile
+    // With two wavefronts per SIMD (NW >= 6) the second one runs half a block behind the first
+    // (see the main loop), which needs a third tile buffer.
+    constexpr bool ROLES = NW >= 6 && RB == 1;
+    constexpr int NBUF = ROLES ? 3 : 2;
     extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* k_s = smem;                                   // [2][KT][KS]
-    unsigned char* v_s = smem + 2 * KT * KS;                     // [2][KT][VS]
-    uint32_t* anc_s = reinterpret_cast<uint32_t*>(smem + 2 * KT * (KS + VS));  // [local node][aw]
+    unsigned char* k_s = smem;                                   // [NBUF][KT][ROWB]
+    unsigned char* v_s = smem + NBUF * TILEB;                    // [NBUF][KT][ROWB]
+    uint32_t* anc_s = reinterpret_cast<uint32_t*>(smem + 2 * NBUF * TILEB);  // [local node][aw]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
     const int n = lane & 31, g2 = lane >> 5;
+#ifdef YGG_TRACE
+    int tr_n = 0;
+#endif
+    TR(0);
 
     // workgroup id -> (stream sigma = (b, kv head, split), row tile); sigma % 8 picks the XCD
     const int wg = blockIdx.x;
@@ -81,7 +133,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, 
     const int64_t rows_total = (int64_t)a.B * a.N * a.Hq;
 
     // rows of this lane: block rb of this wave -> row_base + (wave*RB + rb)*32 + n
-    int64_t rg_of[RB];   // global row index (b, node, q head) or -1
+    int rg_of[RB];       // global row index (b, node, q head) or -1; fits 31 bits (checked on the host)
     int node_of[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -89,7 +141,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, 
         const int i = min(row, R - 1) / a.G;
         const int g = min(row, R - 1) % a.G;
         node_of[rb] = i;
-        rg_of[rb] = row < R ? ((int64_t)b * a.N + i) * a.Hq + hk * a.G + g : -1;
+        rg_of[rb] = row < R ? (b * a.N + i) * a.Hq + hk * a.G + g : -1;
     }
 
     if (k0 >= k1) {  // empty split (uniform over the workgroup): mark the partials as absent
@@ -108,7 +160,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, 
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         if (rg_of[rb] >= 0) {
-            const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const uint16_t*>(a.q) + rg_of[rb] * DH + 8 * g2);
+            const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const uint16_t*>(a.q) + (int64_t)rg_of[rb] * DH + 8 * g2);
 #pragma unroll
             for (int s = 0; s < 8; ++s) qreg[rb][s] = qp[2 * s];
         } else {
@@ -131,149 +183,272 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, 
         }
     }
 
-    const int64_t tok_stride = (int64_t)a.Hkv * DH;  // elements between consecutive tokens
     const uint16_t* kc = static_cast<const uint16_t*>(a.k_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH;
     const uint16_t* vc = static_cast<const uint16_t*>(a.v_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH;
     const uint16_t* kt = static_cast<const uint16_t*>(a.k_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH;
     const uint16_t* vt = static_cast<const uint16_t*>(a.v_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH;
 
-    uint4 kst[PIECES], vst[PIECES];
-    auto load_tile = [&](int tile_base) {
+    // Direct-to-LDS tile fill: wave-instruction `inst` brings rows 4*inst .. 4*inst+3 of the tile;
+    // lane l lands at byte 1024*inst + 16*l, i.e. row 4*inst + l/16, slot' = l%16, and therefore
+    // fetches the slot that the row's permutation maps there.  Rows past the end of the split are
+    // skipped (their K garbage is masked; V was zeroed once so that 0 * stale stays finite).
+    const uint32_t k_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)k_s;  // LDS byte addresses
+    const uint32_t v_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)v_s;
+    // Addresses are a wave-uniform 64-bit base (one sequence's K or V slab) plus a 32-bit byte offset;
+    // the host checks that a slab stays below 4 GiB.
+    const uint32_t tok_bytes = (uint32_t)a.Hkv * DH * 2;
+    auto fill_tile = [&](int buf, int tile_base) {
 #pragma unroll
-        for (int it = 0; it < PIECES; ++it) {
-            const int pid = tid + it * THREADS;
-            const int row = pid >> 4, col = pid & 15;
+        for (int inst = wave; inst < KT / 4; inst += NW) {
+            const int row = 4 * inst + (lane >> 4);
+            const int slotp = lane & 15;
+            const int j0 = tile_base + 4 * inst;     // wave-uniform first key of these four rows
             const int j = tile_base + row;
-            kst[it] = make_uint4(0, 0, 0, 0);
-            vst[it] = make_uint4(0, 0, 0, 0);
-            if (pid < KT * 16 && j < k1) {
-                const int64_t off = (j < L ? (int64_t)j : (int64_t)(j - L)) * tok_stride + col * 8;
-                kst[it] = *reinterpret_cast<const uint4*>((j < L ? kc : kt) + off);
-                vst[it] = *reinterpret_cast<const uint4*>((j < L ? vc : vt) + off);
+            const uint32_t kcol = 16 * (slotp ^ (row & 15));
+            const uint32_t vcol = 16 * (slotp ^ ((row & 7) << 1));
+            const uint32_t kdst = __builtin_amdgcn_readfirstlane(k_lds + buf * TILEB + inst * 1024);
+            const uint32_t vdst = __builtin_amdgcn_readfirstlane(v_lds + buf * TILEB + inst * 1024);
+            if (j0 + 4 <= min(L, k1)) {              // four cache rows (the common case)
+                const uint32_t off = (uint32_t)j * tok_bytes;
+                dma_load16(kc, off + kcol, kdst);
+                dma_load16(vc, off + vcol, vdst);
+            } else {                                 // tree rows, the end of the split, or a mix
+                if (j < min(L, k1)) {
+                    const uint32_t off = (uint32_t)j * tok_bytes;
+                    dma_load16(kc, off + kcol, kdst);
+                    dma_load16(vc, off + vcol, vdst);
+                }
+                if (j >= L && j < k1) {
+                    const uint32_t off = (uint32_t)(j - L) * tok_bytes;
+                    dma_load16(kt, off + kcol, kdst);
+                    dma_load16(vt, off + vcol, vdst);
+                }
             }
         }
     };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int it = 0; it < PIECES; ++it) {
-            const int pid = tid + it * THREADS;
-            const int row = pid >> 4, col = pid & 15;
-            if (pid < KT * 16) {
-                *reinterpret_cast<uint4*>(k_s + (buf * KT + row) * KS + col * 16) = kst[it];
-                *reinterpret_cast<uint4*>(v_s + (buf * KT + row) * VS + col * 16) = vst[it];
-            }
-        }
-    };
+    for (int x = tid; x < NBUF * TILEB / 16; x += THREADS) reinterpret_cast<uint4*>(v_s)[x] = make_uint4(0, 0, 0, 0);
 
     f32x16 o[RB][4];
-    float m_run[RB], l_run[RB];
+    float m_ref[RB], l_run[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        m_run[rb] = -INFINITY;
+        m_ref[rb] = -INFINITY;
         l_run[rb] = 0.f;
 #pragma unroll
         for (int db = 0; db < 4; ++db) o[rb][db] = f32x16{};
     }
     const float c_scale = a.scale * kLog2e;
 
-    const int ntiles = (k1 - k0 + KT - 1) / KT;
-    load_tile(k0);
-    store_tile(0);
-    __syncthreads();  // also publishes anc_s
+    // ---- the pipeline over 32-key blocks ---------------------------------------------------------
+    // Each wavefront alternates between a vector phase (LDS operand reads issued, then the softmax
+    // of block j) and a matrix phase (O^T += V^T.P^T of block j, then S^T of block j+1), so that the
+    // two wavefronts resident on a SIMD keep its matrix pipe and its vector pipe busy in turn.
+    //
+    // Softmax uses a per-row reference m_ref that is only raised when the running maximum exceeds
+    // it by more than kRescaleGap (in log2 units): p = 2^(x - m_ref) may then be as large as
+    // 2^kRescaleGap, which fp32 sums and bf16 weights hold without loss, and O and l -- which
+    // carry the same reference -- are rescaled only in that rare, wave-uniform branch.  The result
+    // O / l and lse = m_ref ln 2 + ln l do not depend on the reference.
+    const int j16 = lane & 15;
+    // K operand of step s: row n, slot 2s+g2 -> slot' = (2s+g2) ^ (n&15) = 2*(s ^ (n&15)>>1) + (g2 ^ (n&1))
+    const int k_lane_off = n * ROWB + 16 * (g2 ^ (n & 1));
+    const int k_pair_xor = ((n & 15) >> 1) << 5;
+    // V operand: row z = 4*g2 + j16/4 (+ multiples of 8), 32-byte pair 2*db + (lane/16)%2 -> pair' = pair ^ (z&7)
+    const int v_z = 4 * g2 + (j16 >> 2);
+    const int v_lane_off = v_z * ROWB + 8 * (j16 & 3);
+    const int v_pair = (lane >> 4) & 1;
 
-    for (int t = 0; t < ntiles; ++t) {
-        const int tile_base = k0 + t * KT;
-        const int buf = t & 1;
-        if (t + 1 < ntiles) load_tile(tile_base + KT);
-        const bool clean = tile_base + KT <= min(L, k1);  // whole tile inside the prefix
-
-#pragma unroll 1
-        for (int kb = 0; kb < KT / 32; ++kb) {
-            const unsigned char* kbuf = k_s + (buf * KT + kb * 32 + n) * KS + 16 * g2;
-            f32x16 st[RB];
+    auto read_k = [&](int buf, int kb, bf16x8 (&ka)[8]) {
+        const unsigned char* kbuf = k_s + buf * TILEB + kb * 32 * ROWB + k_lane_off;
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) st[rb] = f32x16{};
+        for (int s = 0; s < 8; ++s) ka[s] = *reinterpret_cast<const bf16x8*>(kbuf + ((32 * s) ^ k_pair_xor));
+    };
+    // lane j of a 16-lane group addresses key row (j/4), dh 4*(j%4); the transpose read hands each
+    // lane four keys of one dh, i.e. the A operand of O^T += V^T.P^T
+    auto read_v = [&](int buf, int kb, i16x8 (&va)[4][2]) {
+        const unsigned char* vbuf = v_s + buf * TILEB + kb * 32 * ROWB + v_lane_off;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kbuf + 32 * s);
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int m2 = 0; m2 < 2; ++m2) {
+                const unsigned char* p = vbuf + (16 * m2) * ROWB + 32 * ((2 * db + v_pair) ^ v_z);
+                const i16x4 lo = lds_read_tr16(p);
+                const i16x4 hi = lds_read_tr16(p + 8 * ROWB);
+                va[db][m2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+    };
+    auto qk = [&](const bf16x8 (&ka)[8], f32x16 (&st)[RB]) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) st[rb] = f32x16{};
+        if (ABL(4)) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) st[rb][0] = (float)ka[0][0] + (float)ka[7][3];
+            return;
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+                st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[rb][s], st[rb], 0, 0, 0);
+    };
+    auto pv = [&](const i16x8 (&va)[4][2], const i16x8 (&pb)[RB][2]) {
+        if (ABL(4)) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int db = 0; db < 4; ++db) o[rb][db][0] += (float)(va[db][0][0] + va[db][1][7] + pb[rb][0][0] + pb[rb][1][1]);
+            return;
+        }
+#pragma unroll
+        for (int m2 = 0; m2 < 2; ++m2)
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
-                    st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[rb][s], st[rb], 0, 0, 0);
-            }
-
-            i16x8 pb[RB][2];
+                    o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, va[db][m2]), __builtin_bit_cast(bf16x8, pb[rb][m2]), o[rb][db], 0, 0, 0);
+    };
+    // blk0 = first key of the 32-key block; clean = the block's tile lies wholly inside the prefix
+    auto softmax = [&](f32x16 (&st)[RB], i16x8 (&pb)[RB][2], int blk0, bool clean) {
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb) {
-                uint32_t okmask = 0xffffffffu;  // bit u: key u of this 32-key block is visible to this lane's row
-                if (!clean) {
-                    const int blk0 = tile_base + kb * 32;   // first key of the block
-                    const int bt = blk0 - L;                // its tree-node index (negative inside the prefix)
-                    const uint32_t* w = anc_s + (node_of[rb] - i_first) * aw;
-                    if (bt >= 0) {
-                        const int wi = bt >> 5;
-                        const uint64_t w0 = wi < aw ? w[wi] : 0u;
-                        const uint64_t w1 = wi + 1 < aw ? w[wi + 1] : 0u;
-                        okmask = (uint32_t)(((w1 << 32) | w0) >> (bt & 31));
-                    } else if (bt > -32) {                  // block straddles the end of the prefix
-                        okmask = (0xffffffffu >> (32 + bt)) | (w[0] << (-bt));
+        for (int rb = 0; rb < RB; ++rb) {
+            if (ABL(2)) {
+#pragma unroll
+                for (int m2 = 0; m2 < 2; ++m2) {
+                    union { bf16x2 h[4]; i16x8 v; } pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const f32x2 pr = {st[rb][8 * m2 + 2 * e], st[rb][8 * m2 + 2 * e + 1]};
+                        pk.h[e] = __builtin_convertvector(pr, bf16x2);
                     }
-                    const int left = k1 - blk0;             // keys of this block inside the split
-                    if (left < 32) okmask &= left <= 0 ? 0u : (0xffffffffu >> (32 - left));
+                    pb[rb][m2] = pk.v;
                 }
-                float x[16];
-                float mt = -INFINITY;
+                continue;
+            }
+            if (!clean) {
+                uint32_t okmask = 0xffffffffu;  // bit u: key u of this block is visible to this lane's row
+                const int bt = blk0 - L;        // tree-node index of the block's first key (negative inside the prefix)
+                const uint32_t* w = anc_s + (node_of[rb] - i_first) * aw;
+                if (bt >= 0) {
+                    const int wi = bt >> 5;
+                    const uint64_t w0 = wi < aw ? w[wi] : 0u;
+                    const uint64_t w1 = wi + 1 < aw ? w[wi + 1] : 0u;
+                    okmask = (uint32_t)(((w1 << 32) | w0) >> (bt & 31));
+                } else if (bt > -32) {          // block straddles the end of the prefix
+                    okmask = (0xffffffffu >> (32 + bt)) | (w[0] << (-bt));
+                }
+                const int left = k1 - blk0;     // keys of this block inside the split
+                if (left < 32) okmask &= left <= 0 ? 0u : (0xffffffffu >> (32 - left));
+                okmask >>= 4 * g2;  // this half-lane's keys are now bits 8*(v/4) + v%4
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = 8 * (v >> 2) + 4 * g2 + (v & 3);
-                    x[v] = ((okmask >> key) & 1u) ? st[rb][v] * c_scale : -INFINITY;
-                    mt = fmaxf(mt, x[v]);
-                }
-                mt = fmaxf(mt, __shfl_xor(mt, 32));
-                const float mn = fmaxf(m_run[rb], mt);
-                const float ms = mn == -INFINITY ? 0.f : mn;
-                const float alpha = __builtin_amdgcn_exp2f(m_run[rb] - ms);
-                float ps = 0.f;
+                for (int v = 0; v < 16; ++v)
+                    if (!((okmask >> (8 * (v >> 2) + (v & 3))) & 1u)) st[rb][v] = -INFINITY;
+            }
+            float mt = st[rb][0];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    x[v] = __builtin_amdgcn_exp2f(x[v] - ms);
-                    ps += x[v];
-                }
-                l_run[rb] = l_run[rb] * alpha + ps;
-                m_run[rb] = mn;
+            for (int v = 1; v < 16; ++v) mt = fmaxf(mt, st[rb][v]);
+            mt *= c_scale;  // c_scale > 0: the maximum commutes with the scaling
+            if (__any(mt > m_ref[rb] + kRescaleGap)) {
+                const float row_max = fmaxf(mt, __shfl_xor(mt, 32));
+                const bool raise = row_max > m_ref[rb] + kRescaleGap;  // same answer in both half-lanes of a row
+                const float alpha = raise ? __builtin_amdgcn_exp2f(m_ref[rb] - row_max) : 1.f;
+                if (raise) m_ref[rb] = row_max;
+                l_run[rb] *= alpha;
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[rb][db][v] *= alpha;
-#pragma unroll
-                for (int m2 = 0; m2 < 2; ++m2) {
-                    union { uint32_t u[4]; i16x8 v; } pk;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) pk.u[e] = pack_bf16x2(x[8 * m2 + 2 * e], x[8 * m2 + 2 * e + 1]);
-                    pb[rb][m2] = pk.v;
-                }
             }
-
-            // O^T += V^T . P^T ; lane j of a 16-lane group addresses key row (j/4), dh 4*(j%4)
-            const int j16 = lane & 15, blk = (lane >> 4) & 1;
-            const unsigned char* vbuf = v_s + (buf * KT + kb * 32 + 4 * g2 + (j16 >> 2)) * VS + (16 * blk + 4 * (j16 & 3)) * 2;
+            const float ms = m_ref[rb] == -INFINITY ? 0.f : m_ref[rb];  // row with nothing visible so far
+            float ps = 0.f;
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
+            for (int v = 0; v < 16; ++v) {
+                st[rb][v] = __builtin_amdgcn_exp2f(fmaf(st[rb][v], c_scale, -ms));
+                ps += st[rb][v];
+            }
+            l_run[rb] += ps;
 #pragma unroll
-                for (int m2 = 0; m2 < 2; ++m2) {
-                    const unsigned char* p = vbuf + (16 * m2) * VS + db * 64;
-                    const i16x4 lo = lds_read_tr16(p);
-                    const i16x4 hi = lds_read_tr16(p + 8 * VS);
-                    const i16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            for (int m2 = 0; m2 < 2; ++m2) {
+                union { bf16x2 h[4]; i16x8 v; } pk;
 #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-                        o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, va), __builtin_bit_cast(bf16x8, pb[rb][m2]), o[rb][db], 0, 0, 0);
+                for (int e = 0; e < 4; ++e) {
+                    const f32x2 pr = {st[rb][8 * m2 + 2 * e], st[rb][8 * m2 + 2 * e + 1]};
+                    pk.h[e] = __builtin_convertvector(pr, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
                 }
+                pb[rb][m2] = pk.v;
             }
         }
+    };
 
-        if (t + 1 < ntiles) store_tile(buf ^ 1);
-        __syncthreads();
+    static_assert(KT == 64, "the block pipeline below is written for two 32-key blocks per tile");
+    const int ntiles = (k1 - k0 + KT - 1) / KT;
+    const int clean_end = min(L, k1);
+    __syncthreads();  // V buffers zeroed, anc_s published
+    fill_tile(0, k0);
+    dma_wait();
+    __syncthreads();  // tile 0 has landed for everybody
+    if (ntiles > 1) fill_tile(1, k0 + KT);
+
+    // The one barrier per tile ("tile t+1 has landed, tile t-1's buffer may be refilled") sits at a
+    // different point of the program for the two wavefronts of a SIMD: the leading one (late = false)
+    // reaches it after the vector phase of the tile's second block, the trailing one before that
+    // phase.  The barrier therefore holds the trailing wavefront half a block behind, so one is in
+    // its matrix phase while the other is in its vector phase.
+    const bool late = ROLES && wave >= 4;
+    bf16x8 ka[8];
+    i16x8 va[4][2];
+    f32x16 st[RB];
+    i16x8 pb[RB][2];
+    TR(1);
+    read_k(0, 0, ka);
+    qk(ka, st);
+    TR(2);
+    int buf = 0;
+    for (int t = 0; t < ntiles; ++t) {
+        const int tile_base = k0 + t * KT;
+        const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
+        const int buf_fill = NBUF == 2 ? buf : (buf_next + 1 == NBUF ? 0 : buf_next + 1);  // holds tile t+2
+        const bool clean = tile_base + KT <= clean_end;
+        // block 0 of the tile
+        TR(10);
+        read_v(buf, 0, va);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax(st, pb, tile_base, clean);
+        read_k(buf, 1, ka);
+        __builtin_amdgcn_sched_barrier(0);
+        TR(11);
+        pv(va, pb);
+        qk(ka, st);
+        __builtin_amdgcn_sched_barrier(0);
+        TR(12);
+        // block 1 of the tile; the next tile becomes visible before its first K operand is read
+        if (late) {
+            dma_wait();
+            TR(13);
+            if (!ABL(8)) __syncthreads();
+            TR(14);
+            if (t + 2 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 2 * KT);
+            TR(15);
+        }
+        read_v(buf, 1, va);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax(st, pb, tile_base + 32, clean);
+        TR(16);
+        if (!late) {
+            dma_wait();
+            TR(13);
+            if (!ABL(8)) __syncthreads();
+            TR(14);
+            if (t + 2 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 2 * KT);
+            TR(15);
+        }
+        if (t + 1 < ntiles) read_k(buf_next, 0, ka);
+        __builtin_amdgcn_sched_barrier(0);
+        pv(va, pb);
+        if (t + 1 < ntiles) qk(ka, st);
+        __builtin_amdgcn_sched_barrier(0);
+        TR(17);
+        buf = buf_next;
     }
 
     // epilogue: lane (n, g2) holds, for its row, dh = 32 db + 8 (v/4) + 4 g2 + (v%4)
@@ -283,7 +458,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, 
         if (rg_of[rb] < 0) continue;
         if (a.nsplit == 1) {
             const float inv = 1.f / l_tot;
-            uint16_t* op = static_cast<uint16_t*>(a.out) + rg_of[rb] * DH + 4 * g2;
+            uint16_t* op = static_cast<uint16_t*>(a.out) + (int64_t)rg_of[rb] * DH + 4 * g2;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -293,7 +468,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, 
                     w.y = pack_bf16x2(o[rb][db][4 * vq + 2] * inv, o[rb][db][4 * vq + 3] * inv);
                     *reinterpret_cast<uint2*>(op + 32 * db + 8 * vq) = w;
                 }
-            if (a.lse && g2 == 0) a.lse[rg_of[rb]] = m_run[rb] * kLn2 + logf(l_tot);
+            if (a.lse && g2 == 0) a.lse[rg_of[rb]] = m_ref[rb] * kLn2 + logf(l_tot);
         } else {
             float* po = a.part_o + ((int64_t)split * rows_total + rg_of[rb]) * DH + 4 * g2;
 #pragma unroll
@@ -304,7 +479,7 @@ __global__ __launch_bounds__(NW * 64) void attn_mfma_kernel(AttnArgs a, int RT, 
                         make_float4(o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]);
             if (g2 == 0) {
                 float* pml = a.part_ml + ((int64_t)split * rows_total + rg_of[rb]) * 2;
-                pml[0] = m_run[rb] * kLn2;  // natural-log units of the scaled scores
+                pml[0] = m_ref[rb] * kLn2;  // natural-log units of the scaled scores
                 pml[1] = l_tot;
             }
         }
@@ -318,7 +493,8 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int S8 = (S + 7) / 8 * 8;
     const int RW = NW * RB * 32;
     const int nodes_local = (RW + a.G - 1) / a.G + 1;
-    const size_t smem = (size_t)2 * KT * (KS + VS) + (size_t)nodes_local * ((a.N + 31) / 32) * 4;
+    const int nbuf = (NW >= 6 && RB == 1) ? 3 : 2;
+    const size_t smem = (size_t)2 * nbuf * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4;
     auto kern = attn_mfma_kernel<NW, RB, KT>;
     static size_t smem_allowed = 0;  // per instantiation; raising the limit again is harmless
     if (smem > smem_allowed) {
@@ -326,7 +502,18 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
         if (e != hipSuccess) return e;
         smem_allowed = smem;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(NW * 64), smem, st, a, RT, S);
+#ifdef YGG_TRACE
+    if (const char* env = getenv("YGG_TRACE_PTR")) {
+        long long* ptr = reinterpret_cast<long long*>(strtoull(env, nullptr, 0));
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &ptr, sizeof(ptr));
+    }
+
+#endif
+    hipEvent_t ev0, ev1;
+    if (profile_next_events(&ev0, &ev1))
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(NW * 64), (uint32_t)smem, st, ev0, ev1, 0, a, RT, S);
+    else
+        hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(NW * 64), smem, st, a, RT, S);
     return hipGetLastError();
 }
 
@@ -341,6 +528,8 @@ hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st
         case 22: return launch_cfg<2, 2, 64>(a, p, st);
         case 32: return launch_cfg<3, 2, 64>(a, p, st);
         case 41: return launch_cfg<4, 1, 64>(a, p, st);
+        case 61: return launch_cfg<6, 1, 64>(a, p, st);
+        case 81: return launch_cfg<8, 1, 64>(a, p, st);
         case 42: return launch_cfg<4, 2, 64>(a, p, st);
         default: return hipErrorInvalidValue;
     }

@@ -2,8 +2,18 @@
 // is done here other than enqueuing kernels on the caller's stream; nothing synchronises.
 #include "ygg_internal.h"
 
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
 namespace ygg {
 namespace {
+
+struct ProfileState {
+    bool on = false;
+    size_t used = 0;
+    std::vector<hipEvent_t> start, stop;
+} g_profile;
 
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
@@ -45,25 +55,37 @@ AttnPlan plan_attention(const ygg_shape& s) {
     if (p.use_mfma) {
         // query rows that share one K/V stream, and the workgroup shape that wastes the fewest of them
         const int R = s.n_nodes * (s.n_q_heads / s.n_kv_heads);
-        if (R <= 32) { p.waves = 1; p.rblocks = 1; }
-        else if (R <= 64) { p.waves = 2; p.rblocks = 1; }
-        else if (R <= 128) { p.waves = 4; p.rblocks = 1; }
+        p.rblocks = 1;
+        if (R <= 32) p.waves = 1;
+        else if (R <= 64) p.waves = 2;
+        else if (R <= 128) p.waves = 4;
         else {
-            const int cand[3][2] = {{4, 2}, {3, 2}, {2, 2}};
+            // 256-, 192- or 128-row workgroups: fewest padded rows wins, larger workgroup on ties
+            const int cand[3] = {8, 6, 4};
             int best_pad = 0x7fffffff;
-            for (const auto& c : cand) {
-                const int rw = c[0] * c[1] * 32;
+            for (int w : cand) {
+                const int rw = w * 32;
                 const int pad = (R + rw - 1) / rw * rw;
-                if (pad < best_pad) { best_pad = pad; p.waves = c[0]; p.rblocks = c[1]; }
+                if (pad < best_pad) { best_pad = pad; p.waves = w; }
             }
+        }
+        int64_t ns_forced = 0;
+        if (const char* env = getenv("YGG_ATTN_PLAN")) {  // tuning knob: "waves,rblocks[,nsplit]"
+            int w = 0, r = 0, n = 0;
+            const int got = sscanf(env, "%d,%d,%d", &w, &r, &n);
+            const bool known = (r == 2 && w >= 1 && w <= 4) || (r == 1 && (w == 1 || w == 2 || w == 4 || w == 6 || w == 8));
+            if (got >= 2 && known) { p.waves = w; p.rblocks = r; }
+            if (got >= 3 && n >= 1) ns_forced = n;
         }
         const int rw = p.waves * p.rblocks * 32;
         p.row_tiles = (R + rw - 1) / rw;
-        // about two rounds of workgroups over the 256 CUs, at least two key tiles per split
+        // fill the 256 CUs once with eight wavefronts each (more splits only add partial-result traffic),
+        // at least two key tiles per split
         const int64_t per_split = (int64_t)s.batch * s.n_kv_heads * p.row_tiles;
-        const int64_t target = 512 * (p.rblocks == 2 ? 1 : 2);
-        ns = target / per_split;
+        const int64_t wgs_per_cu = p.waves >= 6 ? 1 : 8 / p.waves;
+        ns = 256 * wgs_per_cu / per_split;
         if (ns > tiles / 2) ns = tiles / 2;
+        if (ns_forced) ns = ns_forced < tiles ? ns_forced : tiles;
     } else {
         // vector path: one wavefront per (row, split); aim for ~4096 wavefronts
         ns = (4096 + rows - 1) / rows;
@@ -80,11 +102,54 @@ AttnPlan plan_attention(const ygg_shape& s) {
     return p;
 }
 
+bool profile_next_events(hipEvent_t* start, hipEvent_t* stop) {
+    if (!g_profile.on || g_profile.used >= g_profile.start.size()) return false;
+    *start = g_profile.start[g_profile.used];
+    *stop = g_profile.stop[g_profile.used];
+    ++g_profile.used;
+    return true;
+}
+
 }  // namespace ygg
 
 using namespace ygg;
 
 extern "C" {
+
+int32_t ygg_profile_begin(int32_t max_launches) {
+    if (max_launches < 1 || g_profile.on) return YGG_ERR_SHAPE;
+    g_profile.start.resize((size_t)max_launches);
+    g_profile.stop.resize((size_t)max_launches);
+    for (int32_t i = 0; i < max_launches; ++i) {
+        if (hipEventCreate(&g_profile.start[i]) != hipSuccess || hipEventCreate(&g_profile.stop[i]) != hipSuccess)
+            return YGG_ERR_LAUNCH;
+    }
+    g_profile.used = 0;
+    g_profile.on = true;
+    return YGG_OK;
+}
+
+int32_t ygg_profile_end(double* avg_us, int32_t* n_launches) {
+    if (!g_profile.on) return YGG_ERR_SHAPE;
+    g_profile.on = false;
+    int32_t rc = hipDeviceSynchronize() == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+    double total_ms = 0.0;
+    for (size_t i = 0; i < g_profile.used && rc == YGG_OK; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_profile.start[i], g_profile.stop[i]) != hipSuccess) rc = YGG_ERR_LAUNCH;
+        total_ms += ms;
+    }
+    if (avg_us) *avg_us = g_profile.used ? total_ms * 1000.0 / (double)g_profile.used : 0.0;
+    if (n_launches) *n_launches = (int32_t)g_profile.used;
+    for (size_t i = 0; i < g_profile.start.size(); ++i) {
+        (void)hipEventDestroy(g_profile.start[i]);
+        (void)hipEventDestroy(g_profile.stop[i]);
+    }
+    g_profile.start.clear();
+    g_profile.stop.clear();
+    g_profile.used = 0;
+    return rc;
+}
 
 const char* ygg_status_string(int32_t status) {
     switch (status) {

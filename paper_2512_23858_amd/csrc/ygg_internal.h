@@ -47,6 +47,10 @@ hipError_t launch_attn_vector(const AttnArgs& a, const AttnPlan& p, int dtype, h
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st);
 hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
 
+// Measurement hook: when profiling is on, returns a fresh (start, stop) event pair for the next
+// attention main-kernel launch and true; otherwise false.
+bool profile_next_events(hipEvent_t* start, hipEvent_t* stop);
+
 // ---- equal-growth expansion -------------------------------------------------------------------
 struct ExpandPlan {
     int32_t F;            // frontier rows
