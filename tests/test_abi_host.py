@@ -1,0 +1,124 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes workspaces, and turns every host-checkable mistake into a status code
+before any kernel is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2512_23858_amd as ygg
+from paper_2512_23858_amd.binding import _CShape
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, ERR_NULL, ERR_SHAPE, ERR_UNSUPPORTED, ERR_WORKSPACE = 0, 1, 2, 3, 4
+
+
+def _shape(**kw):
+    base = dict(batch=1, n_q_heads=8, n_kv_heads=2, head_dim=128, depth=3, width=4, n_nodes=13, vocab=1000,
+                kv_dtype=1, softmax_scale=0.0884, kv_capacity=200, max_seq_len=128)
+    base.update(kw)
+    return ygg.Shape(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ygg.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ygg_[a-z_]+)\s*\(", header))
+    assert {"ygg_tree_attention", "ygg_equal_growth_expand", "ygg_accept_and_compact", "ygg_workspace_bytes",
+            "ygg_status_string"} <= declared
+    lib = ygg.load_library()
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in ygg.h but not exported"
+
+
+def test_status_strings_are_distinct():
+    names = {ygg.status_string(i) for i in range(6)}
+    assert len(names) == 6 and ygg.status_string(99) == "unknown status"
+
+
+def test_workspace_sizes():
+    s = _shape()
+    for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT):
+        n = ygg.workspace_bytes(s, op)
+        assert n > 0 and n % 256 == 0
+    assert ygg.workspace_bytes(s, 7) == 0
+    assert ygg.workspace_bytes(_shape(n_q_heads=7), ygg.OP_ATTENTION) == 0          # Hq % Hkv != 0
+    assert ygg.workspace_bytes(_shape(kv_capacity=130), ygg.OP_ATTENTION) == 0      # < max_seq_len + D + 1
+    # the attention workspace holds one fp32 partial (Dh + 2 floats) per split and query row
+    big = _shape(max_seq_len=32768, kv_capacity=32800)
+    rows = big.batch * big.n_nodes * big.n_q_heads
+    assert ygg.workspace_bytes(big, ygg.OP_ATTENTION) >= rows * (128 + 2) * 4
+
+
+def _call_attention(shape, ptrs, ws=None, ws_bytes=0):
+    lib = ygg.load_library()
+    cs = shape.c() if shape is not None else None
+    args = [ctypes.c_void_p(p) for p in ptrs]
+    return lib.ygg_tree_attention(ctypes.byref(cs) if cs is not None else None, *args,
+                                  ctypes.c_void_p(ws), ctypes.c_size_t(ws_bytes), None)
+
+
+FAKE = 0x1000  # never dereferenced on the host: every case below fails validation first
+
+
+def test_attention_rejects_bad_arguments_on_the_host():
+    good = [FAKE] * 8 + [0]   # q kc vc lens kt vt parent out, lse = NULL
+    assert _call_attention(None, good) == ERR_NULL
+    for i in (0, 3, 4, 5, 6, 7):
+        bad = list(good)
+        bad[i] = 0
+        assert _call_attention(_shape(), bad) == ERR_NULL
+    assert _call_attention(_shape(n_q_heads=6, n_kv_heads=4), good) == ERR_SHAPE
+    assert _call_attention(_shape(batch=0), good) == ERR_SHAPE
+    assert _call_attention(_shape(kv_capacity=100), good) == ERR_SHAPE
+    assert _call_attention(_shape(head_dim=96), good) == ERR_UNSUPPORTED
+    assert _call_attention(_shape(kv_dtype=5), good) == ERR_UNSUPPORTED
+    assert _call_attention(_shape(n_nodes=5000), good) == ERR_UNSUPPORTED
+    need = ygg.workspace_bytes(_shape(), ygg.OP_ATTENTION)
+    assert _call_attention(_shape(), good, ws=0, ws_bytes=need) == ERR_WORKSPACE           # missing
+    assert _call_attention(_shape(), good, ws=0x1010, ws_bytes=need) == ERR_WORKSPACE      # misaligned
+    assert _call_attention(_shape(), good, ws=0x1000, ws_bytes=need - 1) == ERR_WORKSPACE  # too small
+
+
+def test_expand_rejects_bad_arguments_on_the_host():
+    lib = ygg.load_library()
+
+    def call(shape, d, ptrs, ws=0x1000, ws_bytes=1 << 30):
+        cs = shape.c()
+        return lib.ygg_equal_growth_expand(ctypes.byref(cs), d, *[ctypes.c_void_p(p) for p in ptrs],
+                                           ctypes.c_void_p(ws), ctypes.c_size_t(ws_bytes), None)
+    good = [FAKE] * 4
+    assert call(_shape(), 0, good) == ERR_SHAPE            # d out of range
+    assert call(_shape(), 4, good) == ERR_SHAPE
+    assert call(_shape(n_nodes=14), 1, good) == ERR_SHAPE  # N != 1 + D*W
+    assert call(_shape(width=65, n_nodes=196), 1, good) == ERR_UNSUPPORTED
+    assert call(_shape(vocab=2, width=4), 1, good) == ERR_SHAPE   # fewer candidates than slots at depth 1
+    assert call(_shape(vocab=600000, width=64, n_nodes=193), 2, good) == ERR_UNSUPPORTED   # too many chunk lists
+    assert call(_shape(), 1, [0] + good[1:]) == ERR_NULL
+    assert call(_shape(), 1, good, ws_bytes=16) == ERR_WORKSPACE
+
+
+def test_accept_rejects_bad_arguments_on_the_host():
+    lib = ygg.load_library()
+
+    def call(shape, n_layers, ptrs, ws=0x1000, ws_bytes=1 << 30):
+        cs = shape.c()
+        return lib.ygg_accept_and_compact(ctypes.byref(cs), n_layers, *[ctypes.c_void_p(p) for p in ptrs],
+                                          ctypes.c_void_p(ws), ctypes.c_size_t(ws_bytes), None)
+    # target_logits target_tokens parent token kt vt kc vc lens alen apath bonus
+    good = [FAKE, 0] + [FAKE] * 10
+    assert call(_shape(), 1, [FAKE, FAKE] + good[2:]) == ERR_NULL      # both targets
+    assert call(_shape(), 1, [0, 0] + good[2:]) == ERR_NULL            # neither
+    assert call(_shape(), -1, good) == ERR_SHAPE
+    bad = list(good)
+    bad[6] = 0
+    assert call(_shape(), 1, bad) == ERR_NULL                          # cache missing while n_layers > 0
+    assert call(_shape(), 1, good, ws_bytes=8) == ERR_WORKSPACE
+    assert call(_shape(head_dim=100), 1, good) == ERR_UNSUPPORTED
+
+
+def test_shape_struct_layout_matches_header():
+    # 10 x int32/float (4 bytes each) + padding to 8 + int64 + int32 + tail padding
+    assert ctypes.sizeof(_CShape) == 56
+    assert _CShape.kv_capacity.offset == 40 and _CShape.max_seq_len.offset == 48
