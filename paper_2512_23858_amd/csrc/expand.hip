@@ -3,21 +3,30 @@
 // Width Selection").
 //
 // Two kernels:
-//   expand_scan   grid (frontier row, vocab chunk): streams the fp32 logits once, coalesced, and
-//                 leaves per chunk {max, sum exp(x - max) in fp64, the chunk's W largest logits}.
-//                 Inside one row the candidate order is the order of the raw logits, so the
-//                 chunk lists are exact whatever the row's normaliser turns out to be.
-//   expand_merge  one workgroup per sequence: per-row log-sum-exp from the chunk statistics,
-//                 then a W-round tournament over the heads of all chunk lists on the fp64 score
-//                 cum[p] + (x - lse_p); ties go to the lower flat index p*V + v.
+//   expand_scan   grid (frontier row, vocab chunk of 4096): streams the fp32 logits once,
+//                 coalesced, and leaves per chunk {max, sum exp(x - max) in fp64, the chunk's W
+//                 largest logits, best first}.  Inside one row the candidate order is the order
+//                 of the raw logits, so the chunk lists are exact whatever the row's normaliser
+//                 turns out to be.
+//   expand_merge  one workgroup per sequence: per-row log-sum-exp from the chunk statistics, the
+//                 fp64 score cum[p] + (x - lse_p) of every list head, the W lists with the best
+//                 heads (no entry of any other list can be among the W best), and finally the W
+//                 best of those lists' W*W entries; ties go to the lower flat index p*V + v.
+//
+// Selection of "the W best of a workgroup's candidates" (used three times) never sorts and has no
+// serial per-element rounds on its main path: each wavefront bisects, with ballots, for the W-th
+// largest of its lanes' maxima (a lower bound of its W-th best candidate), pools the few candidates
+// at or above that threshold in LDS, ranks them against each other, and the four sorted wavefront
+// lists are merged by rank (binary search).  Candidates are ordered by an order-preserving integer
+// key of the value, then by the lower index.
 #include "ygg_internal.h"
 
 namespace ygg {
 namespace {
 
 constexpr int kScanThreads = 256;
-constexpr int kScanElems = 16;  // logits per thread; chunk = 4096
-constexpr long long kNoIndex = 0x7fffffffffffffffLL;
+constexpr int kScanElems = 16;  // logits per thread; chunk = 4096, 1024 consecutive logits per wavefront
+constexpr uint32_t kNone = 0xffffffffu;
 
 struct ChunkStat {
     double sumexp;
@@ -29,207 +38,367 @@ struct Cand {
     int32_t idx;
 };
 
-__device__ __forceinline__ bool beats(double v2, long long i2, double v, long long i) {
-    return v2 > v || (v2 == v && i2 < i);
+// ---- wave-wide reductions on DPP (row shifts and row broadcasts of the 64-wide wavefront) --------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_self(uint32_t v) {
+    // lanes without a valid source (or outside ROW_MASK) keep their own value
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, dpp_or_self<0xb1, 0xf>(v));   // quad_perm [1,0,3,2]
+    v = max(v, dpp_or_self<0x4e, 0xf>(v));   // quad_perm [2,3,0,1]
+    v = max(v, dpp_or_self<0x114, 0xf>(v));  // row_shr:4
+    v = max(v, dpp_or_self<0x118, 0xf>(v));  // row_shr:8   -> lane 15 of every row holds the row maximum
+    v = max(v, dpp_or_self<0x142, 0xa>(v));  // row_bcast:15 into rows 1 and 3
+    v = max(v, dpp_or_self<0x143, 0xc>(v));  // row_bcast:31 into rows 2 and 3 -> lane 63 holds the maximum
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) { return ~wave_max_u32(~v); }
+
+// order-preserving maps to unsigned integers (larger value <-> larger key; -inf is the smallest real key)
+__device__ __forceinline__ uint32_t key_of(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float float_of(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+__device__ __forceinline__ uint64_t key_of(double d) {
+    const uint64_t u = (uint64_t)__double_as_longlong(d);
+    return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double double_of(uint64_t k) {
+    return __longlong_as_double((long long)((k >> 63) ? (k & 0x7fffffffffffffffull) : ~k));
 }
 
-// Workgroup-wide argmax of (value, index): larger value first, lower index on equal values.
-// `slots` holds 2 x 4 entries (double-buffered by round parity); one barrier per call.
-__device__ __forceinline__ void block_argmax(double& v, long long& i, double* slot_v, long long* slot_i, int parity) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const double v2 = __shfl_xor(v, o);
-        const long long i2 = __shfl_xor(i, o);
-        if (beats(v2, i2, v, i)) { v = v2; i = i2; }
-    }
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) { slot_v[parity * 4 + wave] = v; slot_i[parity * 4 + wave] = i; }
-    __syncthreads();
-    v = slot_v[parity * 4];
-    i = slot_i[parity * 4];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) {
-        const double v2 = slot_v[parity * 4 + w];
-        const long long i2 = slot_i[parity * 4 + w];
-        if (beats(v2, i2, v, i)) { v = v2; i = i2; }
-    }
+// exp(t) for t <= 0 in fp64: k = round(t/ln 2), r = t - k ln 2 (two-part constant), Taylor series of
+// degree 13 on |r| <= ln(2)/2 (remainder < 1e-17), scaled by 2^k.  Relative error about 1e-16.
+__device__ __forceinline__ double exp_nonpos(double t) {
+    if (t < -745.0) return 0.0;
+    const double k = rint(t * 1.4426950408889634074);
+    double r = fma(k, -6.93147180369123816490e-01, t);
+    r = fma(k, -1.90821492927058770002e-10, r);
+    double p = 1.0 / 6227020800.0;
+    p = fma(p, r, 1.0 / 479001600.0);
+    p = fma(p, r, 1.0 / 39916800.0);
+    p = fma(p, r, 1.0 / 3628800.0);
+    p = fma(p, r, 1.0 / 362880.0);
+    p = fma(p, r, 1.0 / 40320.0);
+    p = fma(p, r, 1.0 / 5040.0);
+    p = fma(p, r, 1.0 / 720.0);
+    p = fma(p, r, 1.0 / 120.0);
+    p = fma(p, r, 1.0 / 24.0);
+    p = fma(p, r, 1.0 / 6.0);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    p = fma(p, r, 1.0);
+    return ldexp(p, (int)k);
 }
 
+// ---- the W best of a workgroup's candidates ---------------------------------------------------------
+// A candidate: larger key first, then lower tie; key == 0 means "no candidate" (real keys are > 0).
+struct __align__(16) Entry {
+    uint64_t key;
+    uint32_t tie;
+    uint32_t tag;
+};
+__device__ __forceinline__ bool beats(const Entry& a, const Entry& b) {
+    return a.key > b.key || (a.key == b.key && a.tie < b.tie);
+}
+
+constexpr int kPoolCap = 256;  // pooled candidates per wavefront on the fast path
+
+struct TopWShared {
+    Entry pool[4][kPoolCap];
+    Entry list[4][kMaxWidth];  // per-wavefront result, best first
+    int count[4];
+};
+
+// Wave-wide best candidate; lanes without one pass key 0.
+__device__ __forceinline__ Entry wave_best(const Entry& e) {
+    const uint32_t hi = (uint32_t)(e.key >> 32);
+    const uint32_t mh = wave_max_u32(hi);
+    const bool in1 = e.key != 0 && hi == mh;
+    const uint32_t ml = wave_max_u32(in1 ? (uint32_t)e.key : 0u);
+    const bool in2 = in1 && (uint32_t)e.key == ml;
+    const uint32_t mt = wave_min_u32(in2 ? e.tie : kNone);
+    const bool win = in2 && e.tie == mt;
+    const int src = __ffsll((unsigned long long)__ballot(win)) - 1;
+    Entry r;
+    r.key = ((uint64_t)mh << 32) | ml;
+    r.tie = mt;
+    r.tag = src >= 0 ? (uint32_t)__builtin_amdgcn_readlane((int)e.tag, src) : 0u;
+    return r;
+}
+
+// Every lane holds N candidate slots, read through get(k) (key 0 = empty).  Leaves the wavefront's best
+// min(W, #candidates) in sh.list[wave], best first, and their number in sh.count[wave].
+template <int N, typename Get>
+__device__ __forceinline__ void wave_top_w(Get get, int W, int wave, int lane, TopWShared& sh) {
+    uint32_t cmax = 0;   // largest coarse key (top 32 bits) of this lane
+    int have = 0;        // candidates of this lane
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const Entry e = get(k);
+        cmax = max(cmax, (uint32_t)(e.key >> 32));
+        have += e.key != 0;
+    }
+    int tot = have;      // candidates of the wavefront
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o);
+    const int want = min(W, tot);
+    const int wn = min(W, (int)__popcll(__ballot(cmax != 0)));
+    // threshold: the wn-th largest lane maximum -- at least wn candidates lie at or above it
+    uint32_t t = 0;
+    if (wn > 0) {
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t c = t | (1u << bit);
+            if ((int)__popcll(__ballot(cmax >= c)) >= wn) t = c;
+        }
+    }
+    // pool the candidates at or above the threshold
+    int base = 0;
+    const unsigned long long below = __lanemask_lt();
+    bool fits = true;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const Entry e = get(k);
+        const bool sel = wn > 0 && e.key != 0 && (uint32_t)(e.key >> 32) >= t;
+        const unsigned long long m = __ballot(sel);
+        const int pos = base + (int)__popcll(m & below);
+        if (sel && pos < kPoolCap) sh.pool[wave][pos] = e;
+        base += (int)__popcll(m);
+    }
+    fits = base <= kPoolCap && base >= want;
+    if (fits) {
+        // rank the pooled candidates against each other; the best `want` go out in order
+        const int C = base;
+        for (int j0 = 0; j0 < C; j0 += 64) {
+            const int j = j0 + lane;
+            const Entry mine = sh.pool[wave][min(j, C - 1)];
+            int rank = 0;
+            const int C8 = C & ~7;
+            for (int i = 0; i < C8; i += 8) {  // eight independent LDS reads in flight
+#pragma unroll
+                for (int u = 0; u < 8; ++u) rank += beats(sh.pool[wave][i + u], mine);
+            }
+            for (int i = C8; i < C; ++i) rank += beats(sh.pool[wave][i], mine);
+            if (j < C && rank < want) sh.list[wave][rank] = mine;
+        }
+    } else {
+        // Rare (more ties than the pool holds, or too few lanes hold candidates): one candidate per round.
+        uint64_t gone = 0;  // bit k: slot k already emitted
+        for (int r = 0; r < want; ++r) {
+            Entry best = {0, kNone, 0};
+            int bk = -1;
+#pragma unroll
+            for (int k = 0; k < N; ++k) {
+                const Entry e = get(k);
+                if (e.key != 0 && !((gone >> k) & 1ull) && (bk < 0 || beats(e, best))) { best = e; bk = k; }
+            }
+            const Entry w = wave_best(best);
+            if (bk >= 0 && best.key == w.key && best.tie == w.tie) gone |= 1ull << bk;
+            if (lane == 0) sh.list[wave][r] = w;
+        }
+    }
+    if (lane == 0) sh.count[wave] = want;
+}
+
+// After wave_top_w in all four wavefronts and a barrier: rank of entry `lane` of this wavefront's list among
+// the four lists (-1 if this lane holds none); ranks below W are the workgroup's best W, in order.
+__device__ __forceinline__ int merged_rank(const TopWShared& sh, int wave, int lane, Entry& mine) {
+    if (lane >= sh.count[wave]) return -1;
+    mine = sh.list[wave][lane];
+    int rank = lane;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (w == wave) continue;
+        int lo = 0, hi = sh.count[w];  // first position whose entry does not beat `mine`
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (beats(sh.list[w][mid], mine)) lo = mid + 1; else hi = mid;
+        }
+        rank += lo;
+    }
+    return rank;
+}
+
+// ---- scan ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kScanThreads) void expand_scan_kernel(ExpandArgs a) {
-    __shared__ double slot_v[8];
-    __shared__ long long slot_i[8];
     __shared__ double red_d[4];
     __shared__ float red_f[4];
+    __shared__ TopWShared sh;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row = blockIdx.x;  // b*F + p
     const int c = blockIdx.y;
     const int c0 = c * a.chunk;
     const int c1 = min(a.V, c0 + a.chunk);
     const float* x = a.logits + row * a.V;
+    const int w0 = c0 + wave * (kScanElems * 64);  // this wavefront's 1024 consecutive logits
 
     float xv[kScanElems];
-    uint32_t taken = 0;  // bit k set: element k is absent or already emitted
     float tmax = -INFINITY;
 #pragma unroll
     for (int k = 0; k < kScanElems; ++k) {
-        const int idx = c0 + k * kScanThreads + tid;
-        if (idx < c1) {
-            xv[k] = x[idx];
-            tmax = fmaxf(tmax, xv[k]);
-        } else {
-            xv[k] = -INFINITY;
-            taken |= 1u << k;
-        }
+        const int idx = w0 + k * 64 + lane;
+        xv[k] = idx < c1 ? x[idx] : -INFINITY;
+        tmax = fmaxf(tmax, xv[k]);
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) tmax = fmaxf(tmax, __shfl_xor(tmax, o));
-    if (lane == 0) red_f[wave] = tmax;
+    // chunk maximum and sum of exponentials (fp64)
+    const float wmax = float_of(wave_max_u32(key_of(tmax)));
+    if (lane == 0) red_f[wave] = wmax;
     __syncthreads();
     const float cmax = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
-
     double sum = 0.0;
     if (cmax > -INFINITY) {
 #pragma unroll
         for (int k = 0; k < kScanElems; ++k)
-            if (!((taken >> k) & 1u)) sum += exp((double)xv[k] - (double)cmax);
+            if (w0 + k * 64 + lane < c1) sum += exp_nonpos((double)xv[k] - (double)cmax);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
     if (lane == 0) red_d[wave] = sum;
-    __syncthreads();
 
-    const int rounds = min(a.W, c1 - c0);
+    // the chunk's W largest logits: value key in the upper half of the key, vocabulary index as the tie-break
+    auto get = [&](int k) {
+        const int idx = w0 + k * 64 + lane;
+        Entry e;
+        e.key = idx < c1 ? (uint64_t)key_of(xv[k]) << 32 : 0ull;
+        e.tie = (uint32_t)idx;
+        e.tag = 0;
+        return e;
+    };
+    wave_top_w<kScanElems>(get, a.W, wave, lane, sh);
+    __syncthreads();
     if (tid == 0) {
         ChunkStat st;
         st.sumexp = (red_d[0] + red_d[1]) + (red_d[2] + red_d[3]);
         st.maxv = cmax;
-        st.count = rounds;
+        st.count = min(a.W, c1 - c0);
         static_cast<ChunkStat*>(a.stats)[row * a.nchunk + c] = st;
     }
-
-    // thread-local best among the elements not yet emitted (lowest k wins ties = lowest index)
-    auto local_best = [&](double& bv, long long& bi) {
-        bv = -INFINITY;
-        bi = kNoIndex;
-#pragma unroll
-        for (int k = 0; k < kScanElems; ++k) {
-            if (!((taken >> k) & 1u) && (bi == kNoIndex || (double)xv[k] > bv)) {
-                bv = (double)xv[k];
-                bi = c0 + k * kScanThreads + tid;
-            }
-        }
-    };
-    double bv;
-    long long bi;
-    local_best(bv, bi);
-    Cand* out = static_cast<Cand*>(a.cands) + (row * a.nchunk + c) * a.W;
-    for (int r = 0; r < rounds; ++r) {
-        double wv = bv;
-        long long wi = bi;
-        block_argmax(wv, wi, slot_v, slot_i, r & 1);
-        if (tid == 0) {
-            Cand cd;
-            cd.val = (float)wv;
-            cd.idx = (int32_t)wi;
-            out[r] = cd;
-        }
-        if (wi == bi && bi != kNoIndex) {
-            taken |= 1u << (int)((bi - c0 - tid) / kScanThreads);
-            local_best(bv, bi);
-        }
+    Entry mine;
+    const int rank = merged_rank(sh, wave, lane, mine);
+    if (rank >= 0 && rank < a.W) {
+        Cand cd;
+        cd.val = float_of((uint32_t)(mine.key >> 32));
+        cd.idx = (int32_t)mine.tie;
+        static_cast<Cand*>(a.cands)[(row * a.nchunk + c) * a.W + rank] = cd;
     }
 }
 
-constexpr int kMaxListsPerThread = 16;  // 256 threads x 16 = 4096 chunk lists at most
+// ---- merge --------------------------------------------------------------------------------------
+constexpr size_t merge_scratch_bytes(int lpt) { return (size_t)256 * lpt * 12; }
 
+template <int LPT>  // chunk lists per thread
 __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
-    __shared__ double slot_v[8];
-    __shared__ long long slot_i[8];
+    constexpr int KMAX = 256 * LPT;
+    // scratch for the chunk statistics
+    extern __shared__ __align__(16) unsigned char raw[];  // merge_scratch_bytes(LPT)
+    double* ssum = reinterpret_cast<double*>(raw);               // [KMAX]
+    float* smax = reinterpret_cast<float*>(raw + KMAX * 8);      // [KMAX]
+    __shared__ TopWShared sh;
     __shared__ double lse_s[kMaxWidth];
     __shared__ double cum_s[kMaxWidth];
+    __shared__ uint32_t sel[kMaxWidth];       // the lists with the W best heads
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.x;
     const int base_prev = a.d == 1 ? 0 : 1 + (a.d - 2) * a.W;
     const int base_new = 1 + (a.d - 1) * a.W;
-    const ChunkStat* stats = static_cast<const ChunkStat*>(a.stats) + (int64_t)b * a.F * a.nchunk;
-    const Cand* cands = static_cast<const Cand*>(a.cands) + (int64_t)b * a.F * a.nchunk * a.W;
+    const int K = a.F * a.nchunk;  // number of chunk lists, list q = p*nchunk + c
+    const ChunkStat* stats = static_cast<const ChunkStat*>(a.stats) + (int64_t)b * K;
+    const Cand* cands = static_cast<const Cand*>(a.cands) + (int64_t)b * K * a.W;
 
+    // 1. chunk statistics -> per-row log-sum-exp (fixed summation order: deterministic)
+    int cnt[LPT];
+    Cand head[LPT];
+#pragma unroll
+    for (int u = 0; u < LPT; ++u) {
+        const int q = tid + u * 256;
+        cnt[u] = 0;
+        head[u].val = -INFINITY;
+        head[u].idx = 0;
+        if (q < K) {
+            const ChunkStat st = stats[q];
+            smax[q] = st.maxv;
+            ssum[q] = st.sumexp;
+            cnt[u] = st.count;
+            if (st.count > 0) head[u] = cands[(int64_t)q * a.W];
+        }
+    }
+    __syncthreads();
     if (tid < a.F) {
-        const ChunkStat* st = stats + (int64_t)tid * a.nchunk;
+        const int q0 = tid * a.nchunk;
         float mx = -INFINITY;
-        for (int c = 0; c < a.nchunk; ++c) mx = fmaxf(mx, st[c].maxv);
+        for (int c = 0; c < a.nchunk; ++c) mx = fmaxf(mx, smax[q0 + c]);
         double s = 0.0;
         for (int c = 0; c < a.nchunk; ++c)
-            if (st[c].maxv > -INFINITY) s += st[c].sumexp * exp((double)st[c].maxv - (double)mx);
+            if (smax[q0 + c] > -INFINITY) s += ssum[q0 + c] * exp((double)smax[q0 + c] - (double)mx);
         lse_s[tid] = (double)mx + log(s);
         cum_s[tid] = (double)a.cum_logprob[(int64_t)b * a.N + base_prev + tid];
     }
     __syncthreads();
-
-    const int K = a.F * a.nchunk;  // number of chunk lists, list q = p*nchunk + c
-    // per list: current head (entry pos) and the one after it, prefetched
-    double hs[kMaxListsPerThread], ns[kMaxListsPerThread];
-    int hv[kMaxListsPerThread], nv[kMaxListsPerThread];
-    int pos[kMaxListsPerThread], cnt[kMaxListsPerThread];
-    auto score_of = [&](int q, Cand cd) { return cum_s[q / a.nchunk] + ((double)cd.val - lse_s[q / a.nchunk]); };
-#pragma unroll
-    for (int u = 0; u < kMaxListsPerThread; ++u) {
-        const int q = tid + u * 256;
-        hs[u] = ns[u] = -INFINITY;
-        hv[u] = nv[u] = -1;
-        pos[u] = 0;
-        cnt[u] = 0;
-        if (q < K) {
-            cnt[u] = stats[q].count;
-            if (cnt[u] > 0) { const Cand cd = cands[(int64_t)q * a.W]; hs[u] = score_of(q, cd); hv[u] = cd.idx; }
-            if (cnt[u] > 1) { const Cand cd = cands[(int64_t)q * a.W + 1]; ns[u] = score_of(q, cd); nv[u] = cd.idx; }
-        }
-    }
-    auto flat_of = [&](int u) { return (long long)((tid + u * 256) / a.nchunk) * a.V + hv[u]; };
-    int bu = -1;
-    auto local_best = [&](double& bv, long long& bi) {
-        bv = -INFINITY;
-        bi = kNoIndex;
-        bu = -1;
-#pragma unroll
-        for (int u = 0; u < kMaxListsPerThread; ++u) {
-            if (pos[u] < cnt[u]) {
-                const long long f = flat_of(u);
-                if (bu < 0 || beats(hs[u], f, bv, bi)) { bv = hs[u]; bi = f; bu = u; }
-            }
-        }
+    auto entry_of = [&](uint32_t q, Cand cd) {  // fp64 score of candidate cd of list q
+        const int p = (int)q / a.nchunk;
+        Entry e;
+        e.key = key_of(cum_s[p] + ((double)cd.val - lse_s[p]));
+        e.tie = (uint32_t)(p * a.V + cd.idx);   // flat index p*V + v
+        e.tag = q;
+        return e;
     };
-    double bv;
-    long long bi;
-    local_best(bv, bi);
-    for (int r = 0; r < a.W; ++r) {
-        double wv = bv;
-        long long wi = bi;
-        block_argmax(wv, wi, slot_v, slot_i, r & 1);
-        if (tid == 0) {
-            const int64_t node = (int64_t)b * a.N + base_new + r;
-            a.parent_idx[node] = base_prev + (int)(wi / a.V);
-            a.token_ids[node] = (int)(wi % a.V);
-            a.cum_logprob[node] = (float)wv;
-        }
-        if (bu >= 0 && wi == bi) {  // this thread's list won: advance it
+
+    // 2. the lists with the W best heads: no entry of any other list can be among the W best candidates
+    Entry hd[LPT];
 #pragma unroll
-            for (int u = 0; u < kMaxListsPerThread; ++u) {
-                if (u == bu) {
-                    const int q = tid + u * 256;
-                    pos[u] += 1;
-                    hs[u] = ns[u];
-                    hv[u] = nv[u];
-                    if (pos[u] + 1 < cnt[u]) {
-                        const Cand cd = cands[(int64_t)q * a.W + pos[u] + 1];
-                        ns[u] = score_of(q, cd);
-                        nv[u] = cd.idx;
-                    }
-                }
-            }
-            local_best(bv, bi);
+    for (int u = 0; u < LPT; ++u) {
+        const int q = tid + u * 256;
+        hd[u] = Entry{0, kNone, 0};
+        if (q < K && cnt[u] > 0) hd[u] = entry_of((uint32_t)q, head[u]);
+    }
+    wave_top_w<LPT>([&](int u) { return hd[u]; }, a.W, wave, lane, sh);
+    __syncthreads();
+    {
+        Entry mine;
+        const int rank = merged_rank(sh, wave, lane, mine);
+        if (rank >= 0 && rank < a.W) sel[rank] = mine.tag;
+    }
+    const int nsel = min(a.W, sh.count[0] + sh.count[1] + sh.count[2] + sh.count[3]);
+    __syncthreads();  // sel complete; sh and the statistics scratch may be reused
+
+    // 3. the W best entries of the selected lists are the new nodes.  The lists are sorted, so their
+    //    entries are dealt out position-major (slot = pos * nsel + list, thread = slot mod 256): the
+    //    strongest entries then sit in different lanes and the per-wavefront thresholds are tight.
+    //    Every thread fetches its (at most 16) entries in one batch of loads.
+    __shared__ int sel_cnt[kMaxWidth];
+    if (tid < nsel) sel_cnt[tid] = min(a.W, stats[sel[tid]].count);
+    __syncthreads();
+    constexpr int EPT = kMaxWidth * kMaxWidth / 256;  // 16
+    auto get = [&](int u) {
+        const int slot = tid + u * 256;
+        Entry r = {0, kNone, 0};
+        if (slot < nsel * a.W) {
+            const int pos = slot / nsel, s = slot % nsel;
+            if (pos < sel_cnt[s]) r = entry_of(sel[s], cands[(int64_t)sel[s] * a.W + pos]);
+        }
+        return r;
+    };
+    Entry pe[EPT];
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) pe[u] = get(u);
+    wave_top_w<EPT>([&](int u) { return pe[u]; }, a.W, wave, lane, sh);
+    __syncthreads();
+    {
+        Entry mine;
+        const int rank = merged_rank(sh, wave, lane, mine);
+        if (rank >= 0 && rank < a.W) {
+            const int64_t node = (int64_t)b * a.N + base_new + rank;
+            a.parent_idx[node] = base_prev + (int)(mine.tie / (uint32_t)a.V);
+            a.token_ids[node] = (int)(mine.tie % (uint32_t)a.V);
+            a.cum_logprob[node] = (float)double_of(mine.key);
         }
     }
 }
@@ -251,7 +420,22 @@ hipError_t launch_expand(const ExpandArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(expand_scan_kernel, dim3((unsigned)(a.B * a.F), (unsigned)a.nchunk), dim3(kScanThreads), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(expand_merge_kernel, dim3((unsigned)a.B), dim3(256), 0, st, a);
+    const int K = a.F * a.nchunk;
+    const dim3 grid((unsigned)a.B), block(256);
+    if (K <= 256) {
+        hipLaunchKernelGGL(expand_merge_kernel<1>, grid, block, merge_scratch_bytes(1), st, a);
+    } else if (K <= 1024) {
+        hipLaunchKernelGGL(expand_merge_kernel<4>, grid, block, merge_scratch_bytes(4), st, a);
+    } else {
+        static bool raised = false;  // static + dynamic LDS of this instantiation exceeds the 64 KiB default
+        if (!raised) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(expand_merge_kernel<16>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_scratch_bytes(16));
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+        hipLaunchKernelGGL(expand_merge_kernel<16>, grid, block, merge_scratch_bytes(16), st, a);
+    }
     return hipGetLastError();
 }
 

@@ -224,6 +224,7 @@ int32_t ygg_equal_growth_expand(const ygg_shape* s, int32_t d, const float* draf
     const ExpandPlan p = plan_expand(*s, d);
     if ((int64_t)p.F * s->vocab < s->width) return YGG_ERR_SHAPE;
     if ((int64_t)p.F * p.nchunk > 4096) return YGG_ERR_UNSUPPORTED;  // merge holds <= 16 lists per thread
+    if ((int64_t)p.F * s->vocab >= 0x7fffffffLL) return YGG_ERR_UNSUPPORTED;  // flat candidate index is 32 bits
     if ((int64_t)s->batch * p.F > 0x7fffffffLL || p.nchunk > 65535) return YGG_ERR_UNSUPPORTED;
     if (int32_t rc = check_workspace(workspace, workspace_bytes, p.stat_bytes + p.cand_bytes)) return rc;
 
