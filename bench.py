@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="time only the attention calls of a step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB streaming kernel, dst = 2*src (reference point for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); sharding is described in DESIGN.md",
@@ -122,6 +124,14 @@ def main():
         attention_pass()
         ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
                                accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
+
+    if args.calibrate_copy:  # 256 MiB read + 256 MiB written by a plain elementwise kernel (dst = 2 * src)
+        src = torch.ones(256 * 1024 * 1024 // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 2.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     body = attention_pass if args.attention_only else step
     for _ in range(args.warmup):

@@ -37,16 +37,17 @@ namespace {
 #endif
 #ifdef YGG_TRACE
 __device__ long long* g_trace = nullptr;
-#define TR(tag)                                                                                   \
+#define TR(tag) do {} while (0)
+#define TS(i) do { tr_t[i] = __builtin_readcyclecounter(); } while (0)
+#define TS_FLUSH()                                                                                \
     do {                                                                                          \
-        if (blockIdx.x == 0 && lane == 0 && tr_n < 250 && g_trace) {                              \
-            g_trace[(wave * 256 + tr_n) * 2] = (tag);                                             \
-            g_trace[(wave * 256 + tr_n) * 2 + 1] = __builtin_readcyclecounter();                  \
-            ++tr_n;                                                                               \
-        }                                                                                         \
+        if (lane == 0 && g_trace && (blockIdx.x % 37) == 0 && blockIdx.x / 37 < 8)                \
+            for (int i_ = 0; i_ < 8; ++i_) g_trace[((blockIdx.x / 37) * 8 + wave) * 8 + i_] = tr_t[i_]; \
     } while (0)
 #else
 #define TR(tag) do {} while (0)
+#define TS(i) do {} while (0)
+#define TS_FLUSH() do {} while (0)
 #endif
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -74,12 +75,22 @@ __device__ __forceinline__ i16x4 lds_read_tr16(const unsigned char* p) {
 // Direct-to-LDS load of 16 bytes per lane: lane l's data lands at LDS byte address lds_base + 16*l
 // (lds_base is wave-uniform and goes through M0).  Written as inline assembly so that the compiler
 // does not treat every later LDS read as dependent on it (it would wait for the whole prefetch
-// before each operand read); completion is awaited explicitly with dma_wait() before the barrier
+// before each operand read); completion is awaited explicitly with dma_wait_keep() before the barrier
 // that publishes the tile.  The compiler keeps nothing live in M0 on this target.
 __device__ __forceinline__ void dma_load16(const void* base /* wave-uniform */, uint32_t byte_off, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(byte_off), "s"(base) : "memory");
 }
-__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Same with a per-lane 64-bit address.
+__device__ __forceinline__ void dma_load16_flat(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+// Waits until at most KEEP of this wavefront's vector-memory operations are still outstanding (they
+// complete in issue order, so the KEEP youngest may still be in flight).
+template <int KEEP>
+__device__ __forceinline__ void dma_wait_keep() {
+    static_assert(KEEP >= 0 && KEEP <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KEEP) : "memory");
+}
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     // round-to-nearest-even on both halves
@@ -94,22 +105,25 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     constexpr int THREADS = NW * 64;
     constexpr int RW = NW * RB * 32;                             // query rows per workgroup
     constexpr int TILEB = KT * ROWB;                             // bytes of one K (or V) tile
-    // With two wavefronts per SIMD (NW >= 6) the second one runs half a block behind the first
-    // (see the main loop), which needs a third tile buffer.
+    // Tiles are prefetched two ahead (three tile buffers).  With two wavefronts per SIMD (NW >= 6) the
+    // second one runs half a block behind the first (see the main loop), which needs a fourth buffer.
     constexpr bool ROLES = NW >= 6 && RB == 1;
-    constexpr int NBUF = ROLES ? 3 : 2;
+    constexpr int NBUF = ROLES ? 4 : 3;
+    // wavefronts that issue tile fills (a power of two, so that each issues the same number per tile)
+    constexpr int FILLERS = NW >= 8 ? 8 : NW >= 4 ? 4 : NW >= 2 ? 2 : 1;
+    constexpr int PT = 2 * (KT / 4) / FILLERS;  // direct-to-LDS loads per filling wavefront and tile
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* k_s = smem;                                   // [NBUF][KT][ROWB]
     unsigned char* v_s = smem + NBUF * TILEB;                    // [NBUF][KT][ROWB]
-    uint32_t* anc_s = reinterpret_cast<uint32_t*>(smem + 2 * NBUF * TILEB);  // [local node][aw]
+    uint32_t* anc_s = reinterpret_cast<uint32_t*>(smem + 2 * NBUF * TILEB);  // [local node][aw], then parent[N]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
     const int n = lane & 31, g2 = lane >> 5;
 #ifdef YGG_TRACE
-    int tr_n = 0;
+    long long tr_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
 #endif
-    TR(0);
+    TS(0);
 
     // workgroup id -> (stream sigma = (b, kv head, split), row tile); sigma % 8 picks the XCD
     const int wg = blockIdx.x;
@@ -173,60 +187,61 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     const int aw = (a.N + 31) >> 5;
     const int i_first = row_base / a.G;
     const int i_last = min(R - 1, row_base + RW - 1) / a.G;
-    if (k1 > L) {
-        const int32_t* parent = a.parent_idx + (int64_t)b * a.N;
-        for (int t = tid; t <= i_last - i_first; t += THREADS) {
-            uint32_t* w = anc_s + t * aw;
-            for (int x = 0; x < aw; ++x) w[x] = 0;
-            int guard = 0;
-            for (int c = i_first + t; c >= 0 && c < a.N && guard < a.N; c = parent[c], ++guard) w[c >> 5] |= 1u << (c & 31);
-        }
-    }
+    const bool has_tree_keys = k1 > L;  // uniform over the workgroup
+    int32_t* parent_s = reinterpret_cast<int32_t*>(anc_s + (i_last - i_first + 1) * aw);
 
-    const uint16_t* kc = static_cast<const uint16_t*>(a.k_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH;
-    const uint16_t* vc = static_cast<const uint16_t*>(a.v_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH;
-    const uint16_t* kt = static_cast<const uint16_t*>(a.k_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH;
-    const uint16_t* vt = static_cast<const uint16_t*>(a.v_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH;
+    // slab bases of this (sequence, kv head): wave-uniform, pinned to scalar registers
+    auto uniform_ptr = [](const uint16_t* p) {
+        const uint64_t v = (uint64_t)p;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return reinterpret_cast<const uint16_t*>(((uint64_t)hi << 32) | lo);
+    };
+    const uint16_t* kc = uniform_ptr(static_cast<const uint16_t*>(a.k_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH);
+    const uint16_t* vc = uniform_ptr(static_cast<const uint16_t*>(a.v_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH);
+    const uint16_t* kt = uniform_ptr(static_cast<const uint16_t*>(a.k_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH);
+    const uint16_t* vt = uniform_ptr(static_cast<const uint16_t*>(a.v_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH);
 
     // Direct-to-LDS tile fill: wave-instruction `inst` brings rows 4*inst .. 4*inst+3 of the tile;
     // lane l lands at byte 1024*inst + 16*l, i.e. row 4*inst + l/16, slot' = l%16, and therefore
-    // fetches the slot that the row's permutation maps there.  Rows past the end of the split are
-    // skipped (their K garbage is masked; V was zeroed once so that 0 * stale stays finite).
+    // fetches the slot that the row's permutation maps there.  Rows past the end of the split fetch
+    // the split's last key again: their scores are masked, and their V rows are finite, so that a
+    // zero weight times them stays zero.  Every filling wavefront issues exactly PT loads per tile.
     const uint32_t k_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)k_s;  // LDS byte addresses
     const uint32_t v_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)v_s;
     // Addresses are a wave-uniform 64-bit base (one sequence's K or V slab) plus a 32-bit byte offset;
     // the host checks that a slab stays below 4 GiB.
     const uint32_t tok_bytes = (uint32_t)a.Hkv * DH * 2;
     auto fill_tile = [&](int buf, int tile_base) {
+        if (wave >= FILLERS) return;
 #pragma unroll
-        for (int inst = wave; inst < KT / 4; inst += NW) {
+        for (int inst = wave; inst < KT / 4; inst += FILLERS) {
             const int row = 4 * inst + (lane >> 4);
             const int slotp = lane & 15;
             const int j0 = tile_base + 4 * inst;     // wave-uniform first key of these four rows
-            const int j = tile_base + row;
+            const int j = min(tile_base + row, k1 - 1);
             const uint32_t kcol = 16 * (slotp ^ (row & 15));
             const uint32_t vcol = 16 * (slotp ^ ((row & 7) << 1));
             const uint32_t kdst = __builtin_amdgcn_readfirstlane(k_lds + buf * TILEB + inst * 1024);
             const uint32_t vdst = __builtin_amdgcn_readfirstlane(v_lds + buf * TILEB + inst * 1024);
-            if (j0 + 4 <= min(L, k1)) {              // four cache rows (the common case)
+            if (j0 + 4 <= L) {                       // four cache rows (uniform branch, the common case)
                 const uint32_t off = (uint32_t)j * tok_bytes;
                 dma_load16(kc, off + kcol, kdst);
                 dma_load16(vc, off + vcol, vdst);
-            } else {                                 // tree rows, the end of the split, or a mix
-                if (j < min(L, k1)) {
-                    const uint32_t off = (uint32_t)j * tok_bytes;
-                    dma_load16(kc, off + kcol, kdst);
-                    dma_load16(vc, off + vcol, vdst);
-                }
-                if (j >= L && j < k1) {
-                    const uint32_t off = (uint32_t)(j - L) * tok_bytes;
-                    dma_load16(kt, off + kcol, kdst);
-                    dma_load16(vt, off + vcol, vdst);
-                }
+            } else if (j0 >= L) {                    // four tree rows
+                const uint32_t off = (uint32_t)(j - L) * tok_bytes;
+                dma_load16(kt, off + kcol, kdst);
+                dma_load16(vt, off + vcol, vdst);
+            } else {                                 // the four rows straddle the end of the prefix
+                // one load per slab with complementary lanes: still two loads in total per tensor pair
+                const bool in_cache = j < L;
+                const uint32_t off = (uint32_t)(in_cache ? j : j - L) * tok_bytes;
+                const void* kb = in_cache ? (const void*)kc : (const void*)kt;
+                const void* vb = in_cache ? (const void*)vc : (const void*)vt;
+                dma_load16_flat(static_cast<const unsigned char*>(kb) + off + kcol, kdst);
+                dma_load16_flat(static_cast<const unsigned char*>(vb) + off + vcol, vdst);
             }
         }
     };
-    for (int x = tid; x < NBUF * TILEB / 16; x += THREADS) reinterpret_cast<uint4*>(v_s)[x] = make_uint4(0, 0, 0, 0);
 
     f32x16 o[RB][4];
     float m_ref[RB], l_run[RB];
@@ -383,13 +398,30 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     static_assert(KT == 64, "the block pipeline below is written for two 32-key blocks per tile");
     const int ntiles = (k1 - k0 + KT - 1) / KT;
     const int clean_end = min(L, k1);
-    __syncthreads();  // V buffers zeroed, anc_s published
-    fill_tile(0, k0);
-    dma_wait();
-    __syncthreads();  // tile 0 has landed for everybody
-    if (ntiles > 1) fill_tile(1, k0 + KT);
+    TS(1);
+    // prologue: up to three tiles go into flight at once; the ancestor masks are built meanwhile
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        if (i < ntiles) fill_tile(i, k0 + i * KT);
+    if (has_tree_keys) {
+        // one coalesced read of parent_idx; the walks up the tree then stay in LDS
+        const int32_t* parent = a.parent_idx + (int64_t)b * a.N;
+        for (int t = tid; t < a.N; t += THREADS) parent_s[t] = parent[t];
+        __syncthreads();
+        for (int t = tid; t <= i_last - i_first; t += THREADS) {
+            uint32_t* w = anc_s + t * aw;
+            for (int x = 0; x < aw; ++x) w[x] = 0;
+            int guard = 0;
+            for (int c = i_first + t; c >= 0 && c < a.N && guard < a.N; c = parent_s[c], ++guard) w[c >> 5] |= 1u << (c & 31);
+        }
+    }
+    constexpr int PT2 = 2 * PT > 63 ? 63 : 2 * PT;  // a single filling wavefront has 64 loads in flight: wait for one more
+    if (ntiles >= 3) dma_wait_keep<PT2>(); else if (ntiles == 2) dma_wait_keep<PT>(); else dma_wait_keep<0>();
+    TS(2);
+    __syncthreads();  // tile 0 has landed for everybody; anc_s published
+    TS(3);
 
-    // The one barrier per tile ("tile t+1 has landed, tile t-1's buffer may be refilled") sits at a
+    // The one barrier per tile ("tile t+1 has landed, a buffer may be refilled with tile t+3") sits at a
     // different point of the program for the two wavefronts of a SIMD: the leading one (late = false)
     // reaches it after the vector phase of the tile's second block, the trailing one before that
     // phase.  The barrier therefore holds the trailing wavefront half a block behind, so one is in
@@ -407,7 +439,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     for (int t = 0; t < ntiles; ++t) {
         const int tile_base = k0 + t * KT;
         const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
-        const int buf_fill = NBUF == 2 ? buf : (buf_next + 1 == NBUF ? 0 : buf_next + 1);  // holds tile t+2
+        const int buf_fill = (buf + 3) % NBUF;  // receives tile t+3 (with three buffers: the one tile t leaves)
         const bool clean = tile_base + KT <= clean_end;
         // block 0 of the tile
         TR(10);
@@ -423,11 +455,11 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
         TR(12);
         // block 1 of the tile; the next tile becomes visible before its first K operand is read
         if (late) {
-            dma_wait();
+            if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();  // tile t+1 landed, t+2 may be in flight
             TR(13);
             if (!ABL(8)) __syncthreads();
             TR(14);
-            if (t + 2 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 2 * KT);
+            if (t + 3 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 3 * KT);
             TR(15);
         }
         read_v(buf, 1, va);
@@ -435,11 +467,11 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
         softmax(st, pb, tile_base + 32, clean);
         TR(16);
         if (!late) {
-            dma_wait();
+            if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();
             TR(13);
             if (!ABL(8)) __syncthreads();
             TR(14);
-            if (t + 2 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 2 * KT);
+            if (t + 3 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 3 * KT);
             TR(15);
         }
         if (t + 1 < ntiles) read_k(buf_next, 0, ka);
@@ -451,6 +483,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
         buf = buf_next;
     }
 
+    TS(4);
     // epilogue: lane (n, g2) holds, for its row, dh = 32 db + 8 (v/4) + 4 g2 + (v%4)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -484,6 +517,8 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
             }
         }
     }
+    TS(5);
+    TS_FLUSH();
 }
 
 template <int NW, int RB, int KT>
@@ -493,8 +528,8 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int S8 = (S + 7) / 8 * 8;
     const int RW = NW * RB * 32;
     const int nodes_local = (RW + a.G - 1) / a.G + 1;
-    const int nbuf = (NW >= 6 && RB == 1) ? 3 : 2;
-    const size_t smem = (size_t)2 * nbuf * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4;
+    const int nbuf = (NW >= 6 && RB == 1) ? 4 : 3;
+    const size_t smem = (size_t)2 * nbuf * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
     auto kern = attn_mfma_kernel<NW, RB, KT>;
     static size_t smem_allowed = 0;  // per instantiation; raising the limit again is harmless
     if (smem > smem_allowed) {
