@@ -30,7 +30,7 @@ namespace {
 
 // Debug builds (-DYGG_TRACE) record shader-clock stamps of workgroup 0 into a buffer whose address
 // comes from the environment; release builds compile the macro away.
-#ifdef YGG_ABLATE  // timing experiments only: 1 no tile refills, 2 no softmax, 4 no MFMA, 8 no barriers
+#ifdef YGG_ABLATE  // timing experiments only: 1 no tile refills, 2 no softmax, 4 no MFMA, 8 no barriers, 16 no operand re-reads, 32 upper wavefronts idle
 #define ABL(bit) ((YGG_ABLATE) & (bit))
 #else
 #define ABL(bit) 0
@@ -39,6 +39,14 @@ namespace {
 __device__ long long* g_trace = nullptr;
 #define TR(tag) do {} while (0)
 #define TS(i) do { tr_t[i] = __builtin_readcyclecounter(); } while (0)
+#define TP(var) const long long var = __builtin_readcyclecounter()
+#define TP_STORE(t, ...)                                                                          \
+    do {                                                                                          \
+        if (blockIdx.x == 0 && lane == 0 && g_trace && (t) >= 10 && (t) < 14) {                   \
+            const long long v_[] = {__VA_ARGS__};                                                 \
+            for (int i_ = 0; i_ < 8; ++i_) g_trace[512 + ((wave * 4 + (t) - 10) * 8) + i_] = v_[i_]; \
+        }                                                                                         \
+    } while (0)
 #define TS_FLUSH()                                                                                \
     do {                                                                                          \
         if (lane == 0 && g_trace && (blockIdx.x % 37) == 0 && blockIdx.x / 37 < 8)                \
@@ -48,6 +56,8 @@ __device__ long long* g_trace = nullptr;
 #define TR(tag) do {} while (0)
 #define TS(i) do {} while (0)
 #define TS_FLUSH() do {} while (0)
+#define TP(var) do {} while (0)
+#define TP_STORE(t, ...) do {} while (0)
 #endif
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -62,7 +72,8 @@ constexpr int ROWB = 256;  // bytes of one K or V row (head_dim 128, bf16) = 16 
 // LDS tiles are filled by direct-to-LDS loads (64 lanes x 16 bytes land contiguously), so rows are
 // unpadded and bank conflicts are avoided by permuting the 16-byte slots inside each row instead:
 //   K tile: slot' = slot ^ (row & 15)         16 consecutive rows read the same column conflict-free
-//   V tile: slot' = slot ^ ((row & 7) << 1)   transpose reads touch 4..8 rows x 32 bytes
+//   V tile: slot' = slot ^ ((row & 3) << 2)   a transpose read of 32 lanes touches 4 rows x 2 pairs of
+//                                             32 bytes: pair' = pair ^ 2*(row & 3) gives 8 distinct pairs
 // The permutation is applied on the global side (which 16 bytes a lane fetches), never in LDS.
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -107,7 +118,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     constexpr int TILEB = KT * ROWB;                             // bytes of one K (or V) tile
     // Tiles are prefetched two ahead (three tile buffers).  With two wavefronts per SIMD (NW >= 6) the
     // second one runs half a block behind the first (see the main loop), which needs a fourth buffer.
-    constexpr bool ROLES = NW >= 6 && RB == 1;
+    constexpr bool ROLES = false && NW >= 6 && RB == 1;
     constexpr int NBUF = ROLES ? 4 : 3;
     // wavefronts that issue tile fills (a power of two, so that each issues the same number per tile)
     constexpr int FILLERS = NW >= 8 ? 8 : NW >= 4 ? 4 : NW >= 2 ? 2 : 1;
@@ -211,19 +222,40 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     // Addresses are a wave-uniform 64-bit base (one sequence's K or V slab) plus a 32-bit byte offset;
     // the host checks that a slab stays below 4 GiB.
     const uint32_t tok_bytes = (uint32_t)a.Hkv * DH * 2;
+    // per-lane byte offsets of this wavefront's loads inside a tile of cache rows (fast path below)
+    constexpr int FPW = (KT / 4) / FILLERS;  // wave-instructions per filling wavefront, tile and tensor
+    uint32_t fill_k[FPW], fill_v[FPW];
+#pragma unroll
+    for (int it = 0; it < FPW; ++it) {
+        const int row = 4 * (wave + it * FILLERS) + (lane >> 4);
+        const int slotp = lane & 15;
+        fill_k[it] = (uint32_t)row * tok_bytes + 16 * (slotp ^ (row & 15));
+        fill_v[it] = (uint32_t)row * tok_bytes + 16 * (slotp ^ ((row & 3) << 2));
+    }
     auto fill_tile = [&](int buf, int tile_base) {
         if (wave >= FILLERS) return;
+        const uint32_t kdst0 = k_lds + buf * TILEB + wave * 1024, vdst0 = v_lds + buf * TILEB + wave * 1024;
+        if (tile_base + KT <= min(L, k1)) {  // a whole tile of cache rows: base + constant per-lane offsets
+            const uint32_t base = (uint32_t)tile_base * tok_bytes;
 #pragma unroll
-        for (int inst = wave; inst < KT / 4; inst += FILLERS) {
+            for (int it = 0; it < FPW; ++it) {
+                dma_load16(kc, base + fill_k[it], __builtin_amdgcn_readfirstlane(kdst0 + it * FILLERS * 1024));
+                dma_load16(vc, base + fill_v[it], __builtin_amdgcn_readfirstlane(vdst0 + it * FILLERS * 1024));
+            }
+            return;
+        }
+#pragma unroll
+        for (int it = 0; it < FPW; ++it) {
+            const int inst = wave + it * FILLERS;
             const int row = 4 * inst + (lane >> 4);
             const int slotp = lane & 15;
             const int j0 = tile_base + 4 * inst;     // wave-uniform first key of these four rows
             const int j = min(tile_base + row, k1 - 1);
             const uint32_t kcol = 16 * (slotp ^ (row & 15));
-            const uint32_t vcol = 16 * (slotp ^ ((row & 7) << 1));
-            const uint32_t kdst = __builtin_amdgcn_readfirstlane(k_lds + buf * TILEB + inst * 1024);
-            const uint32_t vdst = __builtin_amdgcn_readfirstlane(v_lds + buf * TILEB + inst * 1024);
-            if (j0 + 4 <= L) {                       // four cache rows (uniform branch, the common case)
+            const uint32_t vcol = 16 * (slotp ^ ((row & 3) << 2));
+            const uint32_t kdst = __builtin_amdgcn_readfirstlane(kdst0 + it * FILLERS * 1024);
+            const uint32_t vdst = __builtin_amdgcn_readfirstlane(vdst0 + it * FILLERS * 1024);
+            if (j0 + 4 <= L) {                       // four cache rows (uniform branch)
                 const uint32_t off = (uint32_t)j * tok_bytes;
                 dma_load16(kc, off + kcol, kdst);
                 dma_load16(vc, off + vcol, vdst);
@@ -232,7 +264,6 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
                 dma_load16(kt, off + kcol, kdst);
                 dma_load16(vt, off + vcol, vdst);
             } else {                                 // the four rows straddle the end of the prefix
-                // one load per slab with complementary lanes: still two loads in total per tensor pair
                 const bool in_cache = j < L;
                 const uint32_t off = (uint32_t)(in_cache ? j : j - L) * tok_bytes;
                 const void* kb = in_cache ? (const void*)kc : (const void*)kt;
@@ -268,12 +299,14 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     // K operand of step s: row n, slot 2s+g2 -> slot' = (2s+g2) ^ (n&15) = 2*(s ^ (n&15)>>1) + (g2 ^ (n&1))
     const int k_lane_off = n * ROWB + 16 * (g2 ^ (n & 1));
     const int k_pair_xor = ((n & 15) >> 1) << 5;
-    // V operand: row z = 4*g2 + j16/4 (+ multiples of 8), 32-byte pair 2*db + (lane/16)%2 -> pair' = pair ^ (z&7)
+    // V operand: row z = 4*g2 + j16/4 (+ multiples of 8), 32-byte pair 2*db + (lane/16)%2 -> pair' = pair ^ 2*(z&3)
     const int v_z = 4 * g2 + (j16 >> 2);
     const int v_lane_off = v_z * ROWB + 8 * (j16 & 3);
     const int v_pair = (lane >> 4) & 1;
+    const int v_px = (v_z & 3) << 1;
 
     auto read_k = [&](int buf, int kb, bf16x8 (&ka)[8]) {
+        if (ABL(16) && (buf | kb)) return;
         const unsigned char* kbuf = k_s + buf * TILEB + kb * 32 * ROWB + k_lane_off;
 #pragma unroll
         for (int s = 0; s < 8; ++s) ka[s] = *reinterpret_cast<const bf16x8*>(kbuf + ((32 * s) ^ k_pair_xor));
@@ -281,12 +314,13 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     // lane j of a 16-lane group addresses key row (j/4), dh 4*(j%4); the transpose read hands each
     // lane four keys of one dh, i.e. the A operand of O^T += V^T.P^T
     auto read_v = [&](int buf, int kb, i16x8 (&va)[4][2]) {
+        if (ABL(16) && (buf | kb)) return;
         const unsigned char* vbuf = v_s + buf * TILEB + kb * 32 * ROWB + v_lane_off;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
             for (int m2 = 0; m2 < 2; ++m2) {
-                const unsigned char* p = vbuf + (16 * m2) * ROWB + 32 * ((2 * db + v_pair) ^ v_z);
+                const unsigned char* p = vbuf + (16 * m2) * ROWB + 32 * ((2 * db + v_pair) ^ v_px);
                 const i16x4 lo = lds_read_tr16(p);
                 const i16x4 hi = lds_read_tr16(p + 8 * ROWB);
                 va[db][m2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -427,6 +461,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     // phase.  The barrier therefore holds the trailing wavefront half a block behind, so one is in
     // its matrix phase while the other is in its vector phase.
     const bool late = ROLES && wave >= 4;
+    const bool idle = ABL(32) && wave >= 4;  // timing experiment: barriers and fills only
     bf16x8 ka[8];
     i16x8 va[4][2];
     f32x16 st[RB];
@@ -442,44 +477,63 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
         const int buf_fill = (buf + 3) % NBUF;  // receives tile t+3 (with three buffers: the one tile t leaves)
         const bool clean = tile_base + KT <= clean_end;
         // block 0 of the tile
-        TR(10);
+        TP(ta0);
+        if (!idle) {
         read_v(buf, 0, va);
         __builtin_amdgcn_sched_barrier(0);
         softmax(st, pb, tile_base, clean);
         read_k(buf, 1, ka);
         __builtin_amdgcn_sched_barrier(0);
-        TR(11);
+        }
+        TP(tb0);
+        if (!idle) {
         pv(va, pb);
         qk(ka, st);
         __builtin_amdgcn_sched_barrier(0);
-        TR(12);
+        }
+        TP(tc0);
+        long long tw0 = 0, tw1 = 0;
         // block 1 of the tile; the next tile becomes visible before its first K operand is read
         if (late) {
             if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();  // tile t+1 landed, t+2 may be in flight
-            TR(13);
+            TP(tx0);
             if (!ABL(8)) __syncthreads();
-            TR(14);
+            TP(tx1);
+#ifdef YGG_TRACE
+            tw0 = tx0; tw1 = tx1;
+#endif
             if (t + 3 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 3 * KT);
             TR(15);
         }
+        if (!idle) {
         read_v(buf, 1, va);
         __builtin_amdgcn_sched_barrier(0);
         softmax(st, pb, tile_base + 32, clean);
+        }
         TR(16);
         if (!late) {
             if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();
-            TR(13);
+            TP(ty0);
             if (!ABL(8)) __syncthreads();
-            TR(14);
+            TP(ty1);
+#ifdef YGG_TRACE
+            tw0 = ty0; tw1 = ty1;
+#endif
             if (t + 3 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 3 * KT);
             TR(15);
         }
+        if (!idle) {
         if (t + 1 < ntiles) read_k(buf_next, 0, ka);
         __builtin_amdgcn_sched_barrier(0);
+        }
+        TP(tb1);
+        if (!idle) {
         pv(va, pb);
         if (t + 1 < ntiles) qk(ka, st);
         __builtin_amdgcn_sched_barrier(0);
-        TR(17);
+        }
+        TP(tc1);
+        TP_STORE(t, ta0, tb0, tc0, tw0, tw1, tb1, tc1, 0);
         buf = buf_next;
     }
 
@@ -528,7 +582,7 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int S8 = (S + 7) / 8 * 8;
     const int RW = NW * RB * 32;
     const int nodes_local = (RW + a.G - 1) / a.G + 1;
-    const int nbuf = (NW >= 6 && RB == 1) ? 4 : 3;
+    const int nbuf = 3;
     const size_t smem = (size_t)2 * nbuf * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
     auto kern = attn_mfma_kernel<NW, RB, KT>;
     static size_t smem_allowed = 0;  // per instantiation; raising the limit again is harmless
