@@ -28,38 +28,6 @@
 namespace ygg {
 namespace {
 
-// Debug builds (-DYGG_TRACE) record shader-clock stamps of workgroup 0 into a buffer whose address
-// comes from the environment; release builds compile the macro away.
-#ifdef YGG_ABLATE  // timing experiments only: 1 no tile refills, 2 no softmax, 4 no MFMA, 8 no barriers, 16 no operand re-reads, 32 upper wavefronts idle
-#define ABL(bit) ((YGG_ABLATE) & (bit))
-#else
-#define ABL(bit) 0
-#endif
-#ifdef YGG_TRACE
-__device__ long long* g_trace = nullptr;
-#define TR(tag) do {} while (0)
-#define TS(i) do { tr_t[i] = __builtin_readcyclecounter(); } while (0)
-#define TP(var) const long long var = __builtin_readcyclecounter()
-#define TP_STORE(t, ...)                                                                          \
-    do {                                                                                          \
-        if (blockIdx.x == 0 && lane == 0 && g_trace && (t) >= 10 && (t) < 14) {                   \
-            const long long v_[] = {__VA_ARGS__};                                                 \
-            for (int i_ = 0; i_ < 8; ++i_) g_trace[512 + ((wave * 4 + (t) - 10) * 8) + i_] = v_[i_]; \
-        }                                                                                         \
-    } while (0)
-#define TS_FLUSH()                                                                                \
-    do {                                                                                          \
-        if (lane == 0 && g_trace && (blockIdx.x % 37) == 0 && blockIdx.x / 37 < 8)                \
-            for (int i_ = 0; i_ < 8; ++i_) g_trace[((blockIdx.x / 37) * 8 + wave) * 8 + i_] = tr_t[i_]; \
-    } while (0)
-#else
-#define TR(tag) do {} while (0)
-#define TS(i) do {} while (0)
-#define TS_FLUSH() do {} while (0)
-#define TP(var) do {} while (0)
-#define TP_STORE(t, ...) do {} while (0)
-#endif
-
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((ext_vector_type(8))) short i16x8;
@@ -111,15 +79,18 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (a >> 16) | (b & 0xffff0000u);
 }
 
-template <int NW, int RB, int KT>
+// NW wavefronts, RB 32-row blocks per wavefront, KT keys per tile, KS key shares: with KS = 2 the
+// wavefronts pair up on the same rows and each takes one of the two 32-key blocks of every tile (a
+// tree of few nodes has too few rows to occupy a workgroup otherwise); the pair's (m, l, O~) are
+// merged through LDS before the result is written.
+template <int NW, int RB, int KT, int KS>
 __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
+    static_assert(KS == 1 || (KS == 2 && NW % 2 == 0 && KT == 64), "key shares: one block of the tile each");
     constexpr int THREADS = NW * 64;
-    constexpr int RW = NW * RB * 32;                             // query rows per workgroup
+    constexpr int NRW = NW / KS;                                 // wavefronts along the rows
+    constexpr int RW = NRW * RB * 32;                            // query rows per workgroup
     constexpr int TILEB = KT * ROWB;                             // bytes of one K (or V) tile
-    // Tiles are prefetched two ahead (three tile buffers).  With two wavefronts per SIMD (NW >= 6) the
-    // second one runs half a block behind the first (see the main loop), which needs a fourth buffer.
-    constexpr bool ROLES = false && NW >= 6 && RB == 1;
-    constexpr int NBUF = ROLES ? 4 : 3;
+    constexpr int NBUF = 3;  // tiles are prefetched two ahead
     // wavefronts that issue tile fills (a power of two, so that each issues the same number per tile)
     constexpr int FILLERS = NW >= 8 ? 8 : NW >= 4 ? 4 : NW >= 2 ? 2 : 1;
     constexpr int PT = 2 * (KT / 4) / FILLERS;  // direct-to-LDS loads per filling wavefront and tile
@@ -131,10 +102,8 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
     const int n = lane & 31, g2 = lane >> 5;
-#ifdef YGG_TRACE
-    long long tr_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-    TS(0);
+    const int wrow = KS == 1 ? wave : wave % NRW;  // position along the rows
+    const int kh = KS == 1 ? 0 : wave / NRW;       // which block of every tile (KS = 2)
 
     // workgroup id -> (stream sigma = (b, kv head, split), row tile); sigma % 8 picks the XCD
     const int wg = blockIdx.x;
@@ -157,12 +126,12 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     const int k1 = min(Tk, k0 + chunk);
     const int64_t rows_total = (int64_t)a.B * a.N * a.Hq;
 
-    // rows of this lane: block rb of this wave -> row_base + (wave*RB + rb)*32 + n
+    // rows of this lane: block rb of this wave -> row_base + (wrow*RB + rb)*32 + n
     int rg_of[RB];       // global row index (b, node, q head) or -1; fits 31 bits (checked on the host)
     int node_of[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
-        const int row = row_base + (wave * RB + rb) * 32 + n;
+        const int row = row_base + (wrow * RB + rb) * 32 + n;
         const int i = min(row, R - 1) / a.G;
         const int g = min(row, R - 1) % a.G;
         node_of[rb] = i;
@@ -172,7 +141,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     if (k0 >= k1) {  // empty split (uniform over the workgroup): mark the partials as absent
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
-            if (rg_of[rb] >= 0 && g2 == 0) {
+            if (rg_of[rb] >= 0 && g2 == 0 && kh == 0) {
                 float* pml = a.part_ml + ((int64_t)split * rows_total + rg_of[rb]) * 2;
                 pml[0] = -INFINITY;
                 pml[1] = 0.f;
@@ -306,7 +275,6 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     const int v_px = (v_z & 3) << 1;
 
     auto read_k = [&](int buf, int kb, bf16x8 (&ka)[8]) {
-        if (ABL(16) && (buf | kb)) return;
         const unsigned char* kbuf = k_s + buf * TILEB + kb * 32 * ROWB + k_lane_off;
 #pragma unroll
         for (int s = 0; s < 8; ++s) ka[s] = *reinterpret_cast<const bf16x8*>(kbuf + ((32 * s) ^ k_pair_xor));
@@ -314,7 +282,6 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     // lane j of a 16-lane group addresses key row (j/4), dh 4*(j%4); the transpose read hands each
     // lane four keys of one dh, i.e. the A operand of O^T += V^T.P^T
     auto read_v = [&](int buf, int kb, i16x8 (&va)[4][2]) {
-        if (ABL(16) && (buf | kb)) return;
         const unsigned char* vbuf = v_s + buf * TILEB + kb * 32 * ROWB + v_lane_off;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
@@ -329,11 +296,6 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     auto qk = [&](const bf16x8 (&ka)[8], f32x16 (&st)[RB]) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) st[rb] = f32x16{};
-        if (ABL(4)) {
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb) st[rb][0] = (float)ka[0][0] + (float)ka[7][3];
-            return;
-        }
 #pragma unroll
         for (int s = 0; s < 8; ++s)
 #pragma unroll
@@ -341,13 +303,6 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
                 st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[rb][s], st[rb], 0, 0, 0);
     };
     auto pv = [&](const i16x8 (&va)[4][2], const i16x8 (&pb)[RB][2]) {
-        if (ABL(4)) {
-#pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int db = 0; db < 4; ++db) o[rb][db][0] += (float)(va[db][0][0] + va[db][1][7] + pb[rb][0][0] + pb[rb][1][1]);
-            return;
-        }
 #pragma unroll
         for (int m2 = 0; m2 < 2; ++m2)
 #pragma unroll
@@ -361,19 +316,6 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     auto softmax = [&](f32x16 (&st)[RB], i16x8 (&pb)[RB][2], int blk0, bool clean) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            if (ABL(2)) {
-#pragma unroll
-                for (int m2 = 0; m2 < 2; ++m2) {
-                    union { bf16x2 h[4]; i16x8 v; } pk;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const f32x2 pr = {st[rb][8 * m2 + 2 * e], st[rb][8 * m2 + 2 * e + 1]};
-                        pk.h[e] = __builtin_convertvector(pr, bf16x2);
-                    }
-                    pb[rb][m2] = pk.v;
-                }
-                continue;
-            }
             if (!clean) {
                 uint32_t okmask = 0xffffffffu;  // bit u: key u of this block is visible to this lane's row
                 const int bt = blk0 - L;        // tree-node index of the block's first key (negative inside the prefix)
@@ -432,7 +374,6 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     static_assert(KT == 64, "the block pipeline below is written for two 32-key blocks per tile");
     const int ntiles = (k1 - k0 + KT - 1) / KT;
     const int clean_end = min(L, k1);
-    TS(1);
     // prologue: up to three tiles go into flight at once; the ancestor masks are built meanwhile
 #pragma unroll
     for (int i = 0; i < 3; ++i)
@@ -451,93 +392,101 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     }
     constexpr int PT2 = 2 * PT > 63 ? 63 : 2 * PT;  // a single filling wavefront has 64 loads in flight: wait for one more
     if (ntiles >= 3) dma_wait_keep<PT2>(); else if (ntiles == 2) dma_wait_keep<PT>(); else dma_wait_keep<0>();
-    TS(2);
     __syncthreads();  // tile 0 has landed for everybody; anc_s published
-    TS(3);
 
-    // The one barrier per tile ("tile t+1 has landed, a buffer may be refilled with tile t+3") sits at a
-    // different point of the program for the two wavefronts of a SIMD: the leading one (late = false)
-    // reaches it after the vector phase of the tile's second block, the trailing one before that
-    // phase.  The barrier therefore holds the trailing wavefront half a block behind, so one is in
-    // its matrix phase while the other is in its vector phase.
-    const bool late = ROLES && wave >= 4;
-    const bool idle = ABL(32) && wave >= 4;  // timing experiment: barriers and fills only
+    // One barrier per tile: "tile t+1 has landed for everybody, and everybody is done with tile t-1's
+    // successor buffer", after which that buffer receives tile t+3.
     bf16x8 ka[8];
     i16x8 va[4][2];
     f32x16 st[RB];
     i16x8 pb[RB][2];
-    TR(1);
-    read_k(0, 0, ka);
-    qk(ka, st);
-    TR(2);
     int buf = 0;
-    for (int t = 0; t < ntiles; ++t) {
-        const int tile_base = k0 + t * KT;
-        const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
-        const int buf_fill = (buf + 3) % NBUF;  // receives tile t+3 (with three buffers: the one tile t leaves)
-        const bool clean = tile_base + KT <= clean_end;
-        // block 0 of the tile
-        TP(ta0);
-        if (!idle) {
-        read_v(buf, 0, va);
-        __builtin_amdgcn_sched_barrier(0);
-        softmax(st, pb, tile_base, clean);
-        read_k(buf, 1, ka);
-        __builtin_amdgcn_sched_barrier(0);
-        }
-        TP(tb0);
-        if (!idle) {
-        pv(va, pb);
+    if constexpr (KS == 1) {
+        read_k(0, 0, ka);
         qk(ka, st);
-        __builtin_amdgcn_sched_barrier(0);
-        }
-        TP(tc0);
-        long long tw0 = 0, tw1 = 0;
-        // block 1 of the tile; the next tile becomes visible before its first K operand is read
-        if (late) {
+        for (int t = 0; t < ntiles; ++t) {
+            const int tile_base = k0 + t * KT;
+            const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
+            const bool clean = tile_base + KT <= clean_end;
+            // block 0 of the tile
+            read_v(buf, 0, va);
+            __builtin_amdgcn_sched_barrier(0);
+            softmax(st, pb, tile_base, clean);
+            read_k(buf, 1, ka);
+            __builtin_amdgcn_sched_barrier(0);
+            pv(va, pb);
+            qk(ka, st);
+            __builtin_amdgcn_sched_barrier(0);
+            // block 1 of the tile; the next tile becomes visible before its first K operand is read
+            read_v(buf, 1, va);
+            __builtin_amdgcn_sched_barrier(0);
+            softmax(st, pb, tile_base + 32, clean);
             if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();  // tile t+1 landed, t+2 may be in flight
-            TP(tx0);
-            if (!ABL(8)) __syncthreads();
-            TP(tx1);
-#ifdef YGG_TRACE
-            tw0 = tx0; tw1 = tx1;
-#endif
-            if (t + 3 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 3 * KT);
-            TR(15);
+            __syncthreads();
+            if (t + 3 < ntiles) fill_tile(buf, tile_base + 3 * KT);  // tile t's buffer: every wavefront has read it
+            if (t + 1 < ntiles) read_k(buf_next, 0, ka);
+            __builtin_amdgcn_sched_barrier(0);
+            pv(va, pb);
+            if (t + 1 < ntiles) qk(ka, st);
+            __builtin_amdgcn_sched_barrier(0);
+            buf = buf_next;
         }
-        if (!idle) {
-        read_v(buf, 1, va);
-        __builtin_amdgcn_sched_barrier(0);
-        softmax(st, pb, tile_base + 32, clean);
-        }
-        TR(16);
-        if (!late) {
+    } else {
+        read_k(0, kh, ka);
+        qk(ka, st);
+        for (int t = 0; t < ntiles; ++t) {
+            const int tile_base = k0 + t * KT;
+            const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
+            const bool clean = tile_base + KT <= clean_end;
+            read_v(buf, kh, va);
+            __builtin_amdgcn_sched_barrier(0);
+            softmax(st, pb, tile_base + 32 * kh, clean);
             if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();
-            TP(ty0);
-            if (!ABL(8)) __syncthreads();
-            TP(ty1);
-#ifdef YGG_TRACE
-            tw0 = ty0; tw1 = ty1;
-#endif
-            if (t + 3 < ntiles && !ABL(1)) fill_tile(buf_fill, tile_base + 3 * KT);
-            TR(15);
+            __syncthreads();
+            if (t + 3 < ntiles) fill_tile(buf, tile_base + 3 * KT);
+            if (t + 1 < ntiles) read_k(buf_next, kh, ka);
+            __builtin_amdgcn_sched_barrier(0);
+            pv(va, pb);
+            if (t + 1 < ntiles) qk(ka, st);
+            __builtin_amdgcn_sched_barrier(0);
+            buf = buf_next;
         }
-        if (!idle) {
-        if (t + 1 < ntiles) read_k(buf_next, 0, ka);
-        __builtin_amdgcn_sched_barrier(0);
+        // Merge of the two key shares of a row block.  Both carry O~ and l relative to their own
+        // reference m_ref; the share of block 1 hands its state over through the (now idle) tile
+        // buffers, lane for lane, and the share of block 0 rescales both to the larger reference.
+        float* xch = reinterpret_cast<float*>(smem) + wrow * (RB * 66 * 64) + lane;  // [wrow][rb][66][64 lanes]
+        __syncthreads();  // every wavefront is done with the tiles
+        if (kh == 1) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) {
+                float* x = xch + rb * 66 * 64;
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) x[(16 * db + v) * 64] = o[rb][db][v];
+                x[64 * 64] = m_ref[rb];
+                x[65 * 64] = l_run[rb];
+            }
         }
-        TP(tb1);
-        if (!idle) {
-        pv(va, pb);
-        if (t + 1 < ntiles) qk(ka, st);
-        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        if (kh == 1) return;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const float* x = xch + rb * 66 * 64;
+            const float m1 = x[64 * 64], l1 = x[65 * 64];
+            const float mm = fmaxf(m_ref[rb], m1);
+            // a share that saw no visible key has m = -inf, l = 0, O~ = 0: weight 0 keeps it out
+            const float w0 = m_ref[rb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref[rb] - mm);
+            const float w1 = m1 == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m1 - mm);
+            m_ref[rb] = mm;
+            l_run[rb] = l_run[rb] * w0 + l1 * w1;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[rb][db][v] = o[rb][db][v] * w0 + x[(16 * db + v) * 64] * w1;
         }
-        TP(tc1);
-        TP_STORE(t, ta0, tb0, tc0, tw0, tw1, tb1, tc1, 0);
-        buf = buf_next;
     }
 
-    TS(4);
     // epilogue: lane (n, g2) holds, for its row, dh = 32 db + 8 (v/4) + 4 g2 + (v%4)
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
@@ -571,33 +520,24 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
             }
         }
     }
-    TS(5);
-    TS_FLUSH();
 }
 
-template <int NW, int RB, int KT>
+template <int NW, int RB, int KT, int KS = 1>
 hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int S = a.B * a.Hkv * a.nsplit;
     const int RT = p.row_tiles;
     const int S8 = (S + 7) / 8 * 8;
-    const int RW = NW * RB * 32;
+    const int RW = NW / KS * RB * 32;
     const int nodes_local = (RW + a.G - 1) / a.G + 1;
-    const int nbuf = 3;
-    const size_t smem = (size_t)2 * nbuf * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
-    auto kern = attn_mfma_kernel<NW, RB, KT>;
+    // three K and three V tile buffers, the ancestor bitmasks and the parent table
+    const size_t smem = (size_t)2 * 3 * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
+    auto kern = attn_mfma_kernel<NW, RB, KT, KS>;
     static size_t smem_allowed = 0;  // per instantiation; raising the limit again is harmless
     if (smem > smem_allowed) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         smem_allowed = smem;
     }
-#ifdef YGG_TRACE
-    if (const char* env = getenv("YGG_TRACE_PTR")) {
-        long long* ptr = reinterpret_cast<long long*>(strtoull(env, nullptr, 0));
-        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &ptr, sizeof(ptr));
-    }
-
-#endif
     hipEvent_t ev0, ev1;
     if (profile_next_events(&ev0, &ev1))
         hipExtLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(NW * 64), (uint32_t)smem, st, ev0, ev1, 0, a, RT, S);
@@ -609,8 +549,11 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
-    const int key = p.waves * 10 + p.rblocks;
+    const int key = p.waves * 10 + p.rblocks + 100 * (p.kshares - 1);
     switch (key) {
+        case 121: return launch_cfg<2, 1, 64, 2>(a, p, st);
+        case 141: return launch_cfg<4, 1, 64, 2>(a, p, st);
+        case 181: return launch_cfg<8, 1, 64, 2>(a, p, st);
         case 11: return launch_cfg<1, 1, 64>(a, p, st);
         case 12: return launch_cfg<1, 2, 64>(a, p, st);
         case 21: return launch_cfg<2, 1, 64>(a, p, st);

@@ -151,24 +151,44 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(AttnArgs a) {
 
 // Merge of the per-split partials: m* = max_s m_s, l* = sum_s l_s e^{m_s - m*},
 // O = sum_s O~_s e^{m_s - m*} / l*, lse = m* + ln l*.  One thread per 4 output elements.
+// Splits are taken eight at a time with all of a group's loads issued before any is used, so a
+// row costs one memory round trip per group instead of one per split; groups are chained with the
+// usual running-maximum rescale.
 template <typename T, int DH>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     constexpr int TPR = DH / 4;  // threads per row
+    constexpr int GS = 8;        // splits per group
     const int64_t rows = (int64_t)a.B * a.N * a.Hq;
     const int64_t r = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
     if (r >= rows) return;
     const int c = (threadIdx.x % TPR) * 4;
-    float mstar = -INFINITY;
-    for (int s = 0; s < a.nsplit; ++s) mstar = fmaxf(mstar, a.part_ml[((int64_t)s * rows + r) * 2]);
-    float lstar = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < a.nsplit; ++s) {
-        const float ms = a.part_ml[((int64_t)s * rows + r) * 2];
-        if (ms == -INFINITY) continue;  // split saw no visible key for this row
-        const float w = expf(ms - mstar);
-        lstar += a.part_ml[((int64_t)s * rows + r) * 2 + 1] * w;
-        const float4 v = *reinterpret_cast<const float4*>(a.part_o + ((int64_t)s * rows + r) * DH + c);
-        o[0] = fmaf(v.x, w, o[0]); o[1] = fmaf(v.y, w, o[1]);
-        o[2] = fmaf(v.z, w, o[2]); o[3] = fmaf(v.w, w, o[3]);
+    float mstar = -INFINITY, lstar = 0.f;
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < a.nsplit; s0 += GS) {
+        float2 ml[GS];
+        float4 v[GS];
+#pragma unroll
+        for (int u = 0; u < GS; ++u) {
+            const int s = min(s0 + u, a.nsplit - 1);  // the tail repeats the last split; its weight is dropped below
+            ml[u] = *reinterpret_cast<const float2*>(a.part_ml + ((int64_t)s * rows + r) * 2);
+            v[u] = *reinterpret_cast<const float4*>(a.part_o + ((int64_t)s * rows + r) * DH + c);
+        }
+        float mg = mstar;
+#pragma unroll
+        for (int u = 0; u < GS; ++u) mg = fmaxf(mg, ml[u].x);
+        if (mg == -INFINITY) continue;  // no split so far saw a visible key for this row
+        const float carry = expf(mstar - mg);  // 0 when nothing was accumulated yet
+        lstar *= carry;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] *= carry;
+        mstar = mg;
+#pragma unroll
+        for (int u = 0; u < GS; ++u) {
+            const float w = (s0 + u < a.nsplit && ml[u].x != -INFINITY) ? expf(ml[u].x - mstar) : 0.f;
+            lstar = fmaf(ml[u].y, w, lstar);
+            o[0] = fmaf(v[u].x, w, o[0]); o[1] = fmaf(v[u].y, w, o[1]);
+            o[2] = fmaf(v[u].z, w, o[2]); o[3] = fmaf(v[u].w, w, o[3]);
+        }
     }
     const float inv = 1.f / lstar;
     if constexpr (sizeof(T) == 4) {

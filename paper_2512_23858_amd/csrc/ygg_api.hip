@@ -56,8 +56,10 @@ AttnPlan plan_attention(const ygg_shape& s) {
         // query rows that share one K/V stream, and the workgroup shape that wastes the fewest of them
         const int R = s.n_nodes * (s.n_q_heads / s.n_kv_heads);
         p.rblocks = 1;
-        if (R <= 32) p.waves = 1;
-        else if (R <= 64) p.waves = 2;
+        p.kshares = 1;
+        // few rows: pairs of wavefronts share a row block and split every key tile between them
+        if (R <= 32) { p.waves = 2; p.kshares = 2; }
+        else if (R <= 64) { p.waves = 4; p.kshares = 2; }
         else if (R <= 128) p.waves = 4;
         else {
             // 256-, 192- or 128-row workgroups: fewest padded rows wins, larger workgroup on ties
@@ -70,14 +72,16 @@ AttnPlan plan_attention(const ygg_shape& s) {
             }
         }
         int64_t ns_forced = 0;
-        if (const char* env = getenv("YGG_ATTN_PLAN")) {  // tuning knob: "waves,rblocks[,nsplit]"
-            int w = 0, r = 0, n = 0;
-            const int got = sscanf(env, "%d,%d,%d", &w, &r, &n);
-            const bool known = (r == 2 && w >= 1 && w <= 4) || (r == 1 && (w == 1 || w == 2 || w == 4 || w == 6 || w == 8));
-            if (got >= 2 && known) { p.waves = w; p.rblocks = r; }
+        if (const char* env = getenv("YGG_ATTN_PLAN")) {  // tuning knob: "waves,rblocks[,nsplit[,kshares]]"
+            int w = 0, r = 0, n = 0, k = 1;
+            const int got = sscanf(env, "%d,%d,%d,%d", &w, &r, &n, &k);
+            if (got < 4) k = 1;
+            const bool known = k == 2 ? (r == 1 && (w == 2 || w == 4 || w == 8))
+                                      : (k == 1 && ((r == 2 && w >= 1 && w <= 4) || (r == 1 && (w == 1 || w == 2 || w == 4 || w == 6 || w == 8))));
+            if (got >= 2 && known) { p.waves = w; p.rblocks = r; p.kshares = k; }
             if (got >= 3 && n >= 1) ns_forced = n;
         }
-        const int rw = p.waves * p.rblocks * 32;
+        const int rw = p.waves / p.kshares * p.rblocks * 32;
         p.row_tiles = (R + rw - 1) / rw;
         // fill the 256 CUs once with eight wavefronts each (more splits only add partial-result traffic),
         // at least two key tiles per split

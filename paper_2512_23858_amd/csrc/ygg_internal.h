@@ -38,6 +38,7 @@ struct AttnPlan {
     int32_t use_mfma;       // 1: bf16 matrix-core kernel, 0: fp32 vector kernel
     int32_t waves;          // MFMA kernel: wavefronts per workgroup
     int32_t rblocks;        // MFMA kernel: 32-row blocks per wavefront
+    int32_t kshares;        // MFMA kernel: 1, or 2 = pairs of wavefronts split every key tile
     int32_t row_tiles;      // MFMA kernel: workgroups along the N*G query rows of one kv head
     size_t part_o_bytes, part_ml_bytes;
 };
