@@ -38,6 +38,12 @@ def attention_work(cfg, lens):
     return nbytes, flops
 
 
+# HBM bytes per launch of the attention main kernel (fetched + written), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs
+# scaled by a streaming kernel of known size; a benchmark run cannot collect counters itself, so the figures measured with
+# the commands recorded in profiles/attn_mfma_hbm_traffic.md are carried here, per BASELINE configuration.
+MEASURED_TRAFFIC_BYTES = {2: 26_450_227, 3: 37_865_267, 4: 177_698_509, 5: 329_497_497}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -179,7 +185,7 @@ def main():
     else:
         bound, peak, unit, ach = "hbm", HBM_PEAK_GBS, "GB/s", nbytes / (kern_us * 1e-6) / 1e9
     roofline = {"bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
-                "traffic": None, "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config), "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
                 "launches_timed": kern_n, "algorithmic_bytes": nbytes, "flops": flops,
                 "gbps": round(nbytes / (kern_us * 1e-6) / 1e9, 1), "tflops": round(flops / (kern_us * 1e-6) / 1e12, 2)}
 

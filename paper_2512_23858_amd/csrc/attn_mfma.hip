@@ -33,6 +33,7 @@ typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((ext_vector_type(8))) short i16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
 constexpr int DH = 128;
@@ -511,8 +512,11 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq)
-                    *reinterpret_cast<float4*>(po + 32 * db + 8 * vq) =
-                        make_float4(o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]);
+                {   // streaming store: the partials are read once, by another kernel, and leaving them
+                    // dirty in L2 only lengthens the write-back at the end of this one
+                    const f32x4 val = {o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]};
+                    __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(po + 32 * db + 8 * vq));
+                }
             if (g2 == 0) {
                 float* pml = a.part_ml + ((int64_t)split * rows_total + rg_of[rb]) * 2;
                 pml[0] = m_ref[rb] * kLn2;  // natural-log units of the scaled scores
@@ -549,20 +553,14 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
-    const int key = p.waves * 10 + p.rblocks + 100 * (p.kshares - 1);
-    switch (key) {
-        case 121: return launch_cfg<2, 1, 64, 2>(a, p, st);
-        case 141: return launch_cfg<4, 1, 64, 2>(a, p, st);
-        case 181: return launch_cfg<8, 1, 64, 2>(a, p, st);
-        case 11: return launch_cfg<1, 1, 64>(a, p, st);
-        case 12: return launch_cfg<1, 2, 64>(a, p, st);
-        case 21: return launch_cfg<2, 1, 64>(a, p, st);
-        case 22: return launch_cfg<2, 2, 64>(a, p, st);
-        case 32: return launch_cfg<3, 2, 64>(a, p, st);
-        case 41: return launch_cfg<4, 1, 64>(a, p, st);
-        case 61: return launch_cfg<6, 1, 64>(a, p, st);
-        case 81: return launch_cfg<8, 1, 64>(a, p, st);
-        case 42: return launch_cfg<4, 2, 64>(a, p, st);
+    if (p.rblocks != 1) return hipErrorInvalidValue;
+    switch (p.waves * 10 + p.kshares) {
+        case 41: return launch_cfg<4, 1, 64, 1>(a, p, st);
+        case 61: return launch_cfg<6, 1, 64, 1>(a, p, st);
+        case 81: return launch_cfg<8, 1, 64, 1>(a, p, st);
+        case 22: return launch_cfg<2, 1, 64, 2>(a, p, st);
+        case 42: return launch_cfg<4, 1, 64, 2>(a, p, st);
+        case 82: return launch_cfg<8, 1, 64, 2>(a, p, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -57,27 +57,26 @@ AttnPlan plan_attention(const ygg_shape& s) {
         const int R = s.n_nodes * (s.n_q_heads / s.n_kv_heads);
         p.rblocks = 1;
         p.kshares = 1;
-        // few rows: pairs of wavefronts share a row block and split every key tile between them
+        // Workgroup shapes, by rows per workgroup: 256 (8 wavefronts), 192 (6), 128 (8 wavefronts in
+        // pairs that split every key tile), 64 and 32 (4 and 2 wavefronts in pairs).  More rows per
+        // workgroup amortise the K/V tile traffic and the per-tile barrier over more matrix work, so
+        // a smaller shape is taken only when it saves a good share of padded rows.
+        auto padded = [R](int rw) { return (R + rw - 1) / rw * rw; };
         if (R <= 32) { p.waves = 2; p.kshares = 2; }
         else if (R <= 64) { p.waves = 4; p.kshares = 2; }
-        else if (R <= 128) p.waves = 4;
+        else if (R <= 128) { p.waves = 8; p.kshares = 2; }
         else {
-            // 256-, 192- or 128-row workgroups: fewest padded rows wins, larger workgroup on ties
-            const int cand[3] = {8, 6, 4};
-            int best_pad = 0x7fffffff;
-            for (int w : cand) {
-                const int rw = w * 32;
-                const int pad = (R + rw - 1) / rw * rw;
-                if (pad < best_pad) { best_pad = pad; p.waves = w; }
-            }
+            p.waves = 8;
+            int best = padded(256);
+            if (padded(128) * 100 <= best * 85) { best = padded(128); p.kshares = 2; }
+            if (padded(192) * 100 <= best * 80) { p.waves = 6; p.kshares = 1; }
         }
         int64_t ns_forced = 0;
         if (const char* env = getenv("YGG_ATTN_PLAN")) {  // tuning knob: "waves,rblocks[,nsplit[,kshares]]"
             int w = 0, r = 0, n = 0, k = 1;
             const int got = sscanf(env, "%d,%d,%d,%d", &w, &r, &n, &k);
             if (got < 4) k = 1;
-            const bool known = k == 2 ? (r == 1 && (w == 2 || w == 4 || w == 8))
-                                      : (k == 1 && ((r == 2 && w >= 1 && w <= 4) || (r == 1 && (w == 1 || w == 2 || w == 4 || w == 6 || w == 8))));
+            const bool known = r == 1 && (k == 2 ? (w == 2 || w == 4 || w == 8) : (k == 1 && (w == 4 || w == 6 || w == 8)));
             if (got >= 2 && known) { p.waves = w; p.rblocks = r; p.kshares = k; }
             if (got >= 3 && n >= 1) ns_forced = n;
         }
