@@ -139,6 +139,33 @@ def expand(D, W, d, draft_logits, parent_idx, token_ids, cum_logprob):
     return margin
 
 
+def attach_pool(B, D, W):
+    """Empty pool state for attach(): room for every offer of all D steps."""
+    cap = W + (D - 1) * W * W
+    return {"score": np.zeros((B, cap), np.float64), "node": np.zeros((B, cap), np.int32),
+            "token": np.zeros((B, cap), np.int32), "count": np.zeros(B, np.int32)}
+
+
+def attach(D, W, t, draft_logits, parent_idx, token_ids, cum_logprob, pool):
+    """One draft step of equal growth with free attachment, in place on the tree arrays and the pool; returns margin[B]."""
+    B, F, V = draft_logits.shape
+    N = 1 + D * W
+    assert F == (1 if t == 1 else W)
+    assert draft_logits.dtype == np.float32 and cum_logprob.dtype == np.float32
+    assert parent_idx.dtype == np.int32 and token_ids.dtype == np.int32
+    assert parent_idx.shape == (B, N) and token_ids.shape == (B, N) and cum_logprob.shape == (B, N)
+    cap = pool["score"].shape[1]
+    assert pool["score"].dtype == np.float64 and pool["node"].dtype == np.int32 and pool["token"].dtype == np.int32
+    assert pool["node"].shape == (B, cap) and pool["token"].shape == (B, cap) and pool["count"].shape == (B,)
+    margin = np.empty(B, np.float64)
+    rc = _load().ygg_oracle_attach(_i32(B), _i32(D), _i32(W), _i32(V), _i32(t), _ptr(draft_logits),
+                                   _ptr(parent_idx), _ptr(token_ids), _ptr(cum_logprob), _ptr(pool["score"]),
+                                   _ptr(pool["node"]), _ptr(pool["token"]), _ptr(pool["count"]), _i32(cap), _ptr(margin))
+    if rc != 0:
+        raise ValueError(f"ygg_oracle_attach failed with {rc}")
+    return margin
+
+
 def accept_compact(path_cols, parent_idx, token_ids, k_tree, v_tree, k_cache, v_cache, seq_lens,
                    target_logits=None, target_tokens=None):
     """Greedy acceptance + compaction; k_cache, v_cache and seq_lens are updated in place.

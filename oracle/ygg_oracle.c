@@ -325,6 +325,116 @@ int ygg_oracle_expand(int32_t B, int32_t D, int32_t W, int32_t V, int32_t d,
 }
 
 /* ------------------------------------------------------------------------ *
+ * Equal growth with free attachment (paper Sec. 4.2, "Draft Width Selection",
+ * taken literally: every draft step grows exactly W leaves, and a leaf may hang
+ * under any node of the partial tree, wherever the path-wise gain is largest).
+ *
+ * Reading: every node, once the drafter has run on it, offers its W most
+ * probable tokens (larger logit first, equal logits: lower token first) as
+ * candidate children, each scored cum[node] + log_softmax(row)[token].  The
+ * pool holds every offer not yet taken.  Step t (1..D):
+ *   1. the rows of draft_logits belong to the nodes added at step t-1 (the root
+ *      for t = 1), in node order; their offers join the pool;
+ *   2. the pool is ordered by (score descending, node*V + token ascending);
+ *   3. the first W entries become nodes 1+(t-1)W .. tW in that order (parent =
+ *      offering node, cum_logprob = score rounded to fp32) and leave the pool.
+ * The pool is kept whole (nothing is ever dropped) and stays sorted.
+ *
+ * pool_score/pool_node/pool_token [B,pool_cap], pool_count [B]: in/out state;
+ * step 1 ignores the incoming count.  margin[b] (optional) = score gap between
+ * the W-th and (W+1)-th entry of the ordered pool (+inf if there is none).
+ * ------------------------------------------------------------------------ */
+typedef struct {
+    float x;
+    int32_t v;
+} logit_t;
+
+static int logit_cmp(const void *a, const void *b)
+{
+    const logit_t *x = (const logit_t *)a, *y = (const logit_t *)b;
+    if (x->x > y->x)
+        return -1;
+    if (x->x < y->x)
+        return 1;
+    return x->v < y->v ? -1 : (x->v > y->v ? 1 : 0);
+}
+
+int ygg_oracle_attach(int32_t B, int32_t D, int32_t W, int32_t V, int32_t t,
+                      const float *draft_logits, int32_t *parent_idx, int32_t *token_ids,
+                      float *cum_logprob, double *pool_score, int32_t *pool_node,
+                      int32_t *pool_token, int32_t *pool_count, int32_t pool_cap, double *margin)
+{
+    if (B < 1 || D < 1 || W < 1 || V < W || t < 1 || t > D || pool_cap < 1)
+        return -1;
+    const int32_t N = 1 + D * W;
+    const int32_t F = t == 1 ? 1 : W;
+    const int32_t base_prev = t == 1 ? 0 : 1 + (t - 2) * W;
+    const int32_t base_new = 1 + (t - 1) * W;
+
+    double *scores = (double *)malloc(sizeof(double) * (size_t)V);
+    logit_t *order = (logit_t *)malloc(sizeof(logit_t) * (size_t)V);
+    cand_t *pool = (cand_t *)malloc(sizeof(cand_t) * (size_t)pool_cap);
+    if (!scores || !order || !pool) {
+        free(scores);
+        free(order);
+        free(pool);
+        return -5;
+    }
+    int rc = 0;
+    for (int32_t b = 0; b < B && rc == 0; ++b) {
+        int32_t n = t == 1 ? 0 : pool_count[b];
+        if (n < 0 || n > pool_cap) {
+            rc = -3;
+            break;
+        }
+        for (int32_t i = 0; i < n; ++i) {
+            pool[i].s = pool_score[(int64_t)b * pool_cap + i];
+            pool[i].flat = (int64_t)pool_node[(int64_t)b * pool_cap + i] * V + pool_token[(int64_t)b * pool_cap + i];
+        }
+        for (int32_t p = 0; p < F; ++p) {
+            const int32_t node = base_prev + p;
+            const float *x = draft_logits + ((int64_t)b * F + p) * V;
+            const float cum = cum_logprob[(int64_t)b * N + node];
+            ygg_oracle_expand_scores(1, V, x, &cum, scores);
+            for (int32_t v = 0; v < V; ++v) {
+                order[v].x = x[v];
+                order[v].v = v;
+            }
+            qsort(order, (size_t)V, sizeof(logit_t), logit_cmp);
+            if (n + W > pool_cap) {
+                rc = -7; /* the caller's pool is too small */
+                break;
+            }
+            for (int32_t k = 0; k < W; ++k) {
+                pool[n].s = scores[order[k].v];
+                pool[n].flat = (int64_t)node * V + order[k].v;
+                ++n;
+            }
+        }
+        if (rc)
+            break;
+        qsort(pool, (size_t)n, sizeof(cand_t), cand_cmp);
+        for (int32_t k = 0; k < W; ++k) {
+            parent_idx[(int64_t)b * N + base_new + k] = (int32_t)(pool[k].flat / V);
+            token_ids[(int64_t)b * N + base_new + k] = (int32_t)(pool[k].flat % V);
+            cum_logprob[(int64_t)b * N + base_new + k] = (float)pool[k].s;
+        }
+        if (margin)
+            margin[b] = n > W ? pool[W - 1].s - pool[W].s : INFINITY;
+        for (int32_t i = W; i < n; ++i) {
+            pool_score[(int64_t)b * pool_cap + i - W] = pool[i].s;
+            pool_node[(int64_t)b * pool_cap + i - W] = (int32_t)(pool[i].flat / V);
+            pool_token[(int64_t)b * pool_cap + i - W] = (int32_t)(pool[i].flat % V);
+        }
+        pool_count[b] = n - W;
+    }
+    free(scores);
+    free(order);
+    free(pool);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ *
  * Greedy acceptance and K/V compaction.
  *
  *   t*[i]    = first index of the maximum of target_logits[i,:]
