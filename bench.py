@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="time only the attention calls of a step")
+    ap.add_argument("--growth", choices=["frontier", "attach"], default="frontier",
+                    help="draft-step rule: children of the previous depth only (default, the metric's definition) "
+                         "or free attachment anywhere in the partial tree")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every call from the host instead of replaying one captured HIP graph per step")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -120,6 +123,11 @@ def main():
     ws = [torch.empty(max(ygg.workspace_bytes(shape, op, n_layers), 256), dtype=torch.uint8, device=dev)
           for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT)]
 
+    ws_attach = pool = None
+    if args.growth == "attach":
+        ws_attach = torch.empty(ygg.workspace_bytes(shape, ygg.OP_ATTACH), dtype=torch.uint8, device=dev)
+        pool = torch.empty(ygg.attach_pool_bytes(shape), dtype=torch.uint8, device=dev)
+
     def attention_pass():
         for layer in range(n_layers):
             ygg.tree_attention(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer], v_tree[layer],
@@ -128,7 +136,10 @@ def main():
     def step():
         lens.copy_(lens0)   # acceptance advances seq_lens; every step starts from the same state
         for d in range(1, D + 1):
-            ygg.equal_growth_expand(shape, d, draft[d - 1], e_parent, e_token, e_cum, ws[1])
+            if pool is None:
+                ygg.equal_growth_expand(shape, d, draft[d - 1], e_parent, e_token, e_cum, ws[1])
+            else:
+                ygg.equal_growth_attach(shape, d, draft[d - 1], e_parent, e_token, e_cum, pool, ws_attach)
         attention_pass()
         ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
                                accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
@@ -170,6 +181,48 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
+
+    # ---------------- the three calls on their own (graph replays), with their algorithmic rates
+    def replay_us(fn, reps=20):
+        if args.no_graph:
+            run = fn
+        else:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                fn()
+            run = g.replay
+        for _ in range(3):
+            run()
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        for _ in range(reps):
+            run()
+        a1.record()
+        torch.cuda.synchronize()
+        return a0.elapsed_time(a1) * 1e3 / reps
+
+    def grow_all():
+        for d in range(1, D + 1):
+            if pool is None:
+                ygg.equal_growth_expand(shape, d, draft[d - 1], e_parent, e_token, e_cum, ws[1])
+            else:
+                ygg.equal_growth_attach(shape, d, draft[d - 1], e_parent, e_token, e_cum, pool, ws_attach)
+
+    def accept_only():
+        lens.copy_(lens0)
+        ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
+                               accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
+
+    ops = None
+    if not args.attention_only:
+        grow_us = replay_us(grow_all)
+        acc_us = replay_us(accept_only)
+        att_us = replay_us(attention_pass)
+        grow_bytes = sum(int(x.numel()) * 4 for x in draft)           # every draft logit read once
+        acc_bytes = int(target.numel()) * 4                            # every target logit read once
+        ops = {"growth_us_per_draft_step": round(grow_us / D, 2), "growth_gbps": round(grow_bytes / (grow_us * 1e-6) / 1e9, 1),
+               "accept_us_per_call": round(acc_us, 2), "accept_argmax_gbps": round(acc_bytes / (acc_us * 1e-6) / 1e9, 1),
+               "attention_us_per_layer": round(att_us / n_layers, 2)}
 
     # ---------------- dominant kernel: same launches again with dispatch-bound events
     ygg.profile_begin(args.steps * n_layers)
@@ -249,6 +302,8 @@ def main():
                    "tree": f"depth {D} x width {W} + root = {N} nodes", "vocab": V, "layers": n_layers,
                    "scope": "attention only" if args.attention_only else "full step"},
         "wall_ms_timed_region": round(wall_ms, 2),
+        "growth": args.growth,
+        "calls": ops,
         "launch": "eager" if args.no_graph else "hip-graph replay of one captured step",
         "host_enqueue_us_per_step_eager": None if host_us_per_step is None else round(host_us_per_step, 1),
         "roofline": roofline, "cpu_baseline": cpu,

@@ -51,7 +51,7 @@ typedef enum {
 
 typedef enum { YGG_F32 = 0, YGG_BF16 = 1 } ygg_dtype;
 
-typedef enum { YGG_OP_ATTENTION = 0, YGG_OP_EXPAND = 1, YGG_OP_ACCEPT = 2 } ygg_op;
+typedef enum { YGG_OP_ATTENTION = 0, YGG_OP_EXPAND = 1, YGG_OP_ACCEPT = 2, YGG_OP_ATTACH = 3 } ygg_op;
 
 typedef struct {
     int32_t batch;         /* B >= 1 sequences, one tree each */
@@ -121,6 +121,33 @@ int32_t ygg_tree_attention(const ygg_shape *shape,
  */
 int32_t ygg_equal_growth_expand(const ygg_shape *shape, int32_t d, const float *draft_logits,
                                 int32_t *parent_idx, int32_t *token_ids, float *cum_logprob,
+                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Equal growth with free attachment: draft step t (1..D) of the Equal-Growth Tree as the paper words
+ * it (Sec. 4.2 "Draft Width Selection": every step grows exactly W_draft leaves, and they may hang
+ * anywhere in the partial tree, at the positions with the largest path-wise gain).  Reading: every
+ * node, once the drafter has run on it, offers its W most probable tokens (larger logit first, equal
+ * logits: lower token first), each scored cum_logprob[node] + log_softmax(row)[token] in fp64; the
+ * pool holds the offers not yet taken.  Step t adds the offers of the nodes grown at step t-1 (the
+ * root for t = 1; F = 1 or W rows of draft_logits, in node order), orders the pool by (score
+ * descending, node*V + token ascending) and turns the first W entries into nodes 1+(t-1)W .. tW in
+ * that order: parent_idx <- offering node, token_ids, cum_logprob <- score rounded to fp32.  Node
+ * depth no longer equals the step; it never exceeds t.
+ *
+ *   draft_logits [B,F,V] fp32; parent_idx, token_ids [B,N] int32 and cum_logprob [B,N] fp32 in/out
+ *   pool         device memory owned by the caller and carried from step to step, at least
+ *                ygg_attach_pool_bytes(shape) bytes, 16-byte aligned.  Step 1 initialises it.  Per
+ *                sequence: int32 count, 12 bytes padding, then W*max(D-1,1) records {double score;
+ *                int32 node; int32 token}, the first `count` valid and ordered best first.  After
+ *                step t it holds the best W*(D-t) untaken offers: an entry of rank r cannot be
+ *                taken before r/W more steps, so nothing else can ever become a node.
+ * Requires N == 1 + D*W, V >= W, N*V < 2^32 and W*F + W*(D-t+1) <= 4096.
+ */
+size_t ygg_attach_pool_bytes(const ygg_shape *shape);
+int32_t ygg_equal_growth_attach(const ygg_shape *shape, int32_t t, const float *draft_logits,
+                                int32_t *parent_idx, int32_t *token_ids, float *cum_logprob,
+                                void *pool, size_t pool_bytes,
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*

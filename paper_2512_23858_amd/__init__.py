@@ -1,12 +1,14 @@
 """MI355X (gfx950) tree-verification hot path of Yggdrasil-style speculative decoding.
 
 The work is done by hand-written HIP kernels behind a C ABI (include/ygg.h, built into
-libygg.so).  This package is only the thin Python binding with the same three entry points;
+libygg.so).  This package is only the thin Python binding with the same entry points;
 PyTorch is used for device memory and streams, nothing else.
 """
 from .binding import (  # noqa: F401
     Shape,
     accept_and_compact,
+    attach_pool_bytes,
+    equal_growth_attach,
     equal_growth_expand,
     lib_path,
     load_library,
@@ -18,4 +20,5 @@ from .binding import (  # noqa: F401
     OP_ATTENTION,
     OP_EXPAND,
     OP_ACCEPT,
+    OP_ATTACH,
 )

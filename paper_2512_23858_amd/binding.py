@@ -13,7 +13,7 @@ from dataclasses import dataclass
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-OP_ATTENTION, OP_EXPAND, OP_ACCEPT = 0, 1, 2
+OP_ATTENTION, OP_EXPAND, OP_ACCEPT, OP_ATTACH = 0, 1, 2, 3
 F32, BF16 = 0, 1
 
 
@@ -74,6 +74,10 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_tree_attention.argtypes = [shp] + [vp] * 9 + [vp, sz, vp]
         lib.ygg_equal_growth_expand.restype = i32
         lib.ygg_equal_growth_expand.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp]
+        lib.ygg_attach_pool_bytes.restype = sz
+        lib.ygg_attach_pool_bytes.argtypes = [shp]
+        lib.ygg_equal_growth_attach.restype = i32
+        lib.ygg_equal_growth_attach.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp, sz, vp]
         lib.ygg_accept_and_compact.restype = i32
         lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
         lib.ygg_profile_begin.restype = i32
@@ -148,6 +152,23 @@ def equal_growth_expand(shape: Shape, d: int, draft_logits, parent_idx, token_id
         _dev(parent_idx, torch.int32, "parent_idx"), _dev(token_ids, torch.int32, "token_ids"),
         _dev(cum_logprob, torch.float32, "cum_logprob"), wsp, wsn, _stream())
     _check(rc, "ygg_equal_growth_expand")
+
+
+def attach_pool_bytes(shape: Shape) -> int:
+    cs = shape.c()
+    return int(load_library().ygg_attach_pool_bytes(ctypes.byref(cs)))
+
+
+def equal_growth_attach(shape: Shape, t: int, draft_logits, parent_idx, token_ids, cum_logprob, pool, workspace=None):
+    """ygg_equal_growth_attach: draft step t with free attachment; fills nodes 1+(t-1)W .. tW and updates `pool`."""
+    cs = shape.c()
+    wsp, wsn = _ws(workspace)
+    pp, pn = _ws(pool)
+    rc = load_library().ygg_equal_growth_attach(
+        ctypes.byref(cs), t, _dev(draft_logits, torch.float32, "draft_logits"),
+        _dev(parent_idx, torch.int32, "parent_idx"), _dev(token_ids, torch.int32, "token_ids"),
+        _dev(cum_logprob, torch.float32, "cum_logprob"), pp, pn, wsp, wsn, _stream())
+    _check(rc, "ygg_equal_growth_attach")
 
 
 def accept_and_compact(shape: Shape, n_layers: int, parent_idx, token_ids, k_tree, v_tree, k_cache, v_cache,

@@ -403,6 +403,132 @@ __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
     }
 }
 
+// ---- equal growth with free attachment -----------------------------------------------------------
+// Every node, once the drafter has run on it, offers its W most probable tokens; the pool holds the
+// offers not yet taken; a step takes the W best of the pool (paper Sec. 4.2: the W new leaves of a
+// step may hang anywhere in the partial tree).  Three kernels per step: expand_scan (above) leaves
+// per-chunk statistics and top-W lists of the new rows, attach_rows turns them into each row's W
+// offers, attach_pool sorts pool + offers, emits the W new nodes and keeps the best W*(D-t) of the
+// rest: an entry of rank r needs r / W more steps before it can be taken and later offers only push
+// it down, so nothing beyond the slots still to be filled can ever be chosen.
+struct __align__(16) Offer {
+    double score;
+    int32_t node;
+    int32_t token;
+};
+constexpr int kPoolHeader = 16;  // bytes: int32 count, padding
+
+template <int EPT>  // list entries per thread: nchunk * W <= 256 * EPT
+__global__ __launch_bounds__(256) void attach_rows_kernel(ExpandArgs a) {
+    __shared__ TopWShared sh;
+    __shared__ double lse_sh;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t row = blockIdx.x;  // b*F + p
+    const int b = (int)(row / a.F), p = (int)(row % a.F);
+    const int node = (a.d == 1 ? 0 : 1 + (a.d - 2) * a.W) + p;
+    const ChunkStat* stats = static_cast<const ChunkStat*>(a.stats) + row * a.nchunk;
+    const Cand* cands = static_cast<const Cand*>(a.cands) + row * a.nchunk * a.W;
+
+    // this thread's list entries, position-major (slot = pos * nchunk + chunk): all loads issued at once
+    Entry pe[EPT];
+#pragma unroll
+    for (int u = 0; u < EPT; ++u) {
+        const int slot = tid + u * 256;
+        pe[u] = Entry{0, kNone, 0};
+        if (slot < a.nchunk * a.W) {
+            const int pos = slot / a.nchunk, c = slot % a.nchunk;
+            const int cnt = min(a.W, min(a.V, (c + 1) * a.chunk) - c * a.chunk);
+            if (pos < cnt) {
+                const Cand cd = cands[c * a.W + pos];
+                pe[u].key = (uint64_t)key_of(cd.val) << 32;  // inside a row the order of the raw logits
+                pe[u].tie = (uint32_t)cd.idx;
+            }
+        }
+    }
+    // log-sum-exp of the row from the chunk statistics: wavefront 0, fixed summation order
+    if (wave == 0) {
+        float mx = -INFINITY;
+        for (int c = lane; c < a.nchunk; c += 64) mx = fmaxf(mx, stats[c].maxv);
+        mx = float_of(wave_max_u32(key_of(mx)));
+        double sum = 0.0;
+        for (int c = lane; c < a.nchunk; c += 64) {
+            const ChunkStat st = stats[c];
+            if (st.maxv > -INFINITY) sum += st.sumexp * exp_nonpos((double)st.maxv - (double)mx);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+        if (lane == 0) lse_sh = (double)mx + log(sum);
+    }
+    wave_top_w<EPT>([&](int u) { return pe[u]; }, a.W, wave, lane, sh);
+    __syncthreads();
+    Entry mine;
+    const int rank = merged_rank(sh, wave, lane, mine);
+    if (rank >= 0 && rank < a.W) {
+        Offer o;
+        const double cum = (double)a.cum_logprob[(int64_t)b * a.N + node];
+        o.score = cum + ((double)float_of((uint32_t)(mine.key >> 32)) - lse_sh);
+        o.node = node;
+        o.token = (int32_t)mine.tie;
+        static_cast<Offer*>(a.offers)[row * a.W + rank] = o;
+    }
+}
+
+// One workgroup per sequence; dynamic LDS holds n2 (a power of two) entries.
+__global__ __launch_bounds__(256) void attach_pool_kernel(ExpandArgs a, int n2) {
+    extern __shared__ __align__(16) unsigned char raw_sort[];
+    Entry* e = reinterpret_cast<Entry*>(raw_sort);
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    unsigned char* pool_b = static_cast<unsigned char*>(a.pool) + (size_t)b * (kPoolHeader + (size_t)a.pool_cap * sizeof(Offer));
+    int32_t* pool_count = reinterpret_cast<int32_t*>(pool_b);
+    Offer* pool = reinterpret_cast<Offer*>(pool_b + kPoolHeader);
+    const Offer* offers = static_cast<const Offer*>(a.offers) + (int64_t)b * a.F * a.W;
+    int n_old = a.d == 1 ? 0 : *pool_count;
+    n_old = n_old < 0 ? 0 : min(n_old, min(a.pool_cap, a.W * (a.D - a.d + 1)));  // what the previous step may have left
+    const int n_new = a.F * a.W;
+    for (int i = tid; i < n2; i += 256) {
+        Entry x = {0, kNone, 0};
+        if (i < n_old + n_new) {
+            const Offer o = i < n_old ? pool[i] : offers[i - n_old];
+            x.key = key_of(o.score);
+            x.tie = (uint32_t)o.node * (uint32_t)a.V + (uint32_t)o.token;
+        }
+        e[i] = x;
+    }
+    __syncthreads();
+    // bitonic sort, best first (larger key, then lower node*V + token); empty slots sink to the end
+    for (int k = 2; k <= n2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < (n2 >> 1); i += 256) {
+                const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+                const int hi = lo | j;
+                const Entry x = e[lo], y = e[hi];
+                const bool down = (lo & k) == 0;
+                if (down ? beats(y, x) : beats(x, y)) { e[lo] = y; e[hi] = x; }
+            }
+            __syncthreads();
+        }
+    const int base_new = 1 + (a.d - 1) * a.W;
+    const int keep = min(a.W * (a.D - a.d), n_old + n_new - a.W);
+    for (int i = tid; i < a.W + keep; i += 256) {
+        const Entry x = e[i];
+        const int node = (int)(x.tie / (uint32_t)a.V), token = (int)(x.tie % (uint32_t)a.V);
+        const double score = double_of(x.key);
+        if (i < a.W) {
+            const int64_t dst = (int64_t)b * a.N + base_new + i;
+            a.parent_idx[dst] = node;
+            a.token_ids[dst] = token;
+            a.cum_logprob[dst] = (float)score;
+        } else {
+            Offer o;
+            o.score = score; o.node = node; o.token = token;
+            pool[i - a.W] = o;
+        }
+    }
+    if (tid == 0) *pool_count = keep;
+}
+
 }  // namespace
 
 ExpandPlan plan_expand(const ygg_shape& s, int32_t d) {
@@ -436,6 +562,32 @@ hipError_t launch_expand(const ExpandArgs& a, hipStream_t st) {
         }
         hipLaunchKernelGGL(expand_merge_kernel<16>, grid, block, merge_scratch_bytes(16), st, a);
     }
+    return hipGetLastError();
+}
+
+size_t attach_offer_bytes(const ygg_shape& s) {
+    return ((size_t)s.batch * (size_t)s.width * (size_t)s.width * sizeof(Offer) + 255) / 256 * 256;
+}
+int64_t attach_pool_capacity(const ygg_shape& s) { return (int64_t)s.width * (s.depth > 1 ? s.depth - 1 : 1); }
+size_t attach_pool_bytes(const ygg_shape& s) {
+    return ((size_t)s.batch * (kPoolHeader + (size_t)attach_pool_capacity(s) * sizeof(Offer)) + 255) / 256 * 256;
+}
+
+hipError_t launch_attach(const ExpandArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(expand_scan_kernel, dim3((unsigned)(a.B * a.F), (unsigned)a.nchunk), dim3(kScanThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int per_row = a.nchunk * a.W;
+    const dim3 rows((unsigned)(a.B * a.F)), block(256);
+    if (per_row <= 256) hipLaunchKernelGGL(attach_rows_kernel<1>, rows, block, 0, st, a);
+    else if (per_row <= 1024) hipLaunchKernelGGL(attach_rows_kernel<4>, rows, block, 0, st, a);
+    else hipLaunchKernelGGL(attach_rows_kernel<16>, rows, block, 0, st, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int n = a.F * a.W + (a.d == 1 ? 0 : a.W * (a.D - a.d + 1));
+    int n2 = 2;
+    while (n2 < n) n2 <<= 1;
+    hipLaunchKernelGGL(attach_pool_kernel, dim3((unsigned)a.B), block, (size_t)n2 * sizeof(Entry), st, a, n2);
     return hipGetLastError();
 }
 

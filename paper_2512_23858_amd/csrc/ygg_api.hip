@@ -180,6 +180,11 @@ size_t ygg_workspace_bytes(const ygg_shape* s, int32_t op, int32_t n_layers) {
             const ExpandPlan p = plan_expand(*s, 2);  // the widest frontier
             return p.stat_bytes + p.cand_bytes;
         }
+        case YGG_OP_ATTACH: {
+            if (check_shape(s, false, true) != YGG_OK) return 0;
+            const ExpandPlan p = plan_expand(*s, 2);
+            return p.stat_bytes + p.cand_bytes + attach_offer_bytes(*s);
+        }
         case YGG_OP_ACCEPT: {
             if (check_shape(s, false, true) != YGG_OK) return 0;
             const AcceptPlan p = plan_accept(*s);
@@ -238,6 +243,40 @@ int32_t ygg_equal_growth_expand(const ygg_shape* s, int32_t d, const float* draf
     a.B = s->batch; a.D = s->depth; a.W = s->width; a.V = s->vocab; a.N = s->n_nodes; a.d = d;
     a.F = p.F; a.chunk = p.chunk; a.nchunk = p.nchunk;
     return launch_expand(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
+size_t ygg_attach_pool_bytes(const ygg_shape* s) {
+    if (!s || check_shape(s, false, true) != YGG_OK || s->depth < 1) return 0;
+    return attach_pool_bytes(*s);
+}
+
+int32_t ygg_equal_growth_attach(const ygg_shape* s, int32_t t, const float* draft_logits, int32_t* parent_idx,
+                                int32_t* token_ids, float* cum_logprob, void* pool, size_t pool_bytes,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (int32_t rc = check_shape(s, false, true)) return rc;
+    if (!draft_logits || !parent_idx || !token_ids || !cum_logprob || !pool) return YGG_ERR_NULL;
+    if (s->depth < 1 || t < 1 || t > s->depth) return YGG_ERR_SHAPE;
+    if ((int64_t)s->n_nodes != 1 + (int64_t)s->depth * s->width) return YGG_ERR_SHAPE;
+    if (s->vocab < s->width) return YGG_ERR_SHAPE;  // every row must be able to offer W tokens
+    const ExpandPlan p = plan_expand(*s, t);
+    if ((int64_t)p.nchunk * s->width > 4096) return YGG_ERR_UNSUPPORTED;   // a row's chunk lists: <= 16 entries per thread
+    if ((int64_t)s->n_nodes * s->vocab > 0xffffffffLL) return YGG_ERR_UNSUPPORTED;  // node*V + token is 32 bits
+    if ((int64_t)s->batch * p.F > 0x7fffffffLL || p.nchunk > 65535) return YGG_ERR_UNSUPPORTED;
+    // pool + offers are sorted in one workgroup's LDS: at most 4096 entries
+    if ((int64_t)p.F * s->width + (int64_t)s->width * (s->depth - t + 1) > 4096) return YGG_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(pool) & 15u) != 0 || pool_bytes < attach_pool_bytes(*s)) return YGG_ERR_WORKSPACE;
+    const size_t offer_bytes = attach_offer_bytes(*s);
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.stat_bytes + p.cand_bytes + offer_bytes)) return rc;
+
+    ExpandArgs a{};
+    a.logits = draft_logits; a.parent_idx = parent_idx; a.token_ids = token_ids; a.cum_logprob = cum_logprob;
+    a.stats = workspace;
+    a.cands = static_cast<char*>(workspace) + p.stat_bytes;
+    a.offers = static_cast<char*>(workspace) + p.stat_bytes + p.cand_bytes;
+    a.pool = pool; a.pool_cap = (int32_t)attach_pool_capacity(*s);
+    a.B = s->batch; a.D = s->depth; a.W = s->width; a.V = s->vocab; a.N = s->n_nodes; a.d = t;
+    a.F = p.F; a.chunk = p.chunk; a.nchunk = p.nchunk;
+    return launch_attach(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
 }
 
 int32_t ygg_accept_and_compact(const ygg_shape* s, int32_t n_layers, const float* target_logits,

@@ -67,10 +67,18 @@ struct ExpandArgs {
     float* cum_logprob;
     void* stats;
     void* cands;
+    void* offers;      // free attachment only: [B*F][W] {double score; int32 node; int32 token}
+    void* pool;        // free attachment only: per sequence {int32 count, pad to 16 B, pool_cap offers}
+    int32_t pool_cap;
     int32_t B, D, W, V, N, d, F, chunk, nchunk;
 };
 ExpandPlan plan_expand(const ygg_shape& s, int32_t d);
 hipError_t launch_expand(const ExpandArgs& a, hipStream_t st);
+// free attachment: d is the draft step; rows belong to the nodes added at step d-1
+size_t attach_offer_bytes(const ygg_shape& s);
+int64_t attach_pool_capacity(const ygg_shape& s);
+size_t attach_pool_bytes(const ygg_shape& s);
+hipError_t launch_attach(const ExpandArgs& a, hipStream_t st);
 
 // ---- acceptance + compaction ------------------------------------------------------------------
 struct AcceptPlan {

@@ -39,7 +39,7 @@ def test_status_strings_are_distinct():
 
 def test_workspace_sizes():
     s = _shape()
-    for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT):
+    for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT, ygg.OP_ATTACH):
         n = ygg.workspace_bytes(s, op)
         assert n > 0 and n % 256 == 0
     assert ygg.workspace_bytes(s, 7) == 0
@@ -97,6 +97,31 @@ def test_expand_rejects_bad_arguments_on_the_host():
     assert call(_shape(vocab=600000, width=64, n_nodes=193), 2, good) == ERR_UNSUPPORTED   # too many chunk lists
     assert call(_shape(), 1, [0] + good[1:]) == ERR_NULL
     assert call(_shape(), 1, good, ws_bytes=16) == ERR_WORKSPACE
+
+
+def test_attach_rejects_bad_arguments_on_the_host():
+    lib = ygg.load_library()
+
+    def call(shape, t, ptrs, pool=0x2000, pool_bytes=1 << 30, ws=0x1000, ws_bytes=1 << 30):
+        cs = shape.c()
+        return lib.ygg_equal_growth_attach(ctypes.byref(cs), t, *[ctypes.c_void_p(p) for p in ptrs],
+                                           ctypes.c_void_p(pool), ctypes.c_size_t(pool_bytes),
+                                           ctypes.c_void_p(ws), ctypes.c_size_t(ws_bytes), None)
+    good = [FAKE] * 4
+    assert call(_shape(), 0, good) == ERR_SHAPE            # step out of range
+    assert call(_shape(), 4, good) == ERR_SHAPE
+    assert call(_shape(n_nodes=14), 1, good) == ERR_SHAPE  # N != 1 + D*W
+    assert call(_shape(vocab=3, width=4), 1, good) == ERR_SHAPE          # a row cannot offer W tokens
+    assert call(_shape(width=64, n_nodes=193, vocab=9000), 2, good) == ERR_UNSUPPORTED   # W*W offers + pool > 4096 entries
+    assert call(_shape(vocab=600000, width=32, n_nodes=97), 2, good) == ERR_UNSUPPORTED  # a row's chunk lists > 4096 entries
+    assert call(_shape(), 1, [0] + good[1:]) == ERR_NULL
+    assert call(_shape(), 1, good, pool=0) == ERR_NULL
+    assert call(_shape(), 1, good, pool=0x2008) == ERR_WORKSPACE          # pool not 16-byte aligned
+    assert call(_shape(), 1, good, pool_bytes=64) == ERR_WORKSPACE
+    assert call(_shape(), 1, good, ws_bytes=16) == ERR_WORKSPACE
+    s = _shape()
+    assert ygg.attach_pool_bytes(s) >= s.batch * (16 + s.width * (s.depth - 1) * 16)
+    assert ygg.workspace_bytes(s, ygg.OP_ATTACH) > ygg.workspace_bytes(s, ygg.OP_EXPAND)
 
 
 def test_accept_rejects_bad_arguments_on_the_host():

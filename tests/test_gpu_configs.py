@@ -76,6 +76,17 @@ def test_expansion_full_size(config):
         assert ((blk >= lo) & (blk <= hi)).all()
 
 
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
+def test_free_attachment_full_size(config):
+    """Equal growth with free attachment on the same draft logits: tree and pool after every step."""
+    from test_gpu_attach import attach_both
+    cfg = wl.CONFIGS[config]
+    parent, _, _ = attach_both(cfg)
+    W = cfg.width
+    for i in range(1, cfg.n_nodes):    # a leaf hangs under any node grown in an earlier step
+        assert np.all((parent[:, i] >= 0) & (parent[:, i] < 1 + ((i - 1) // W) * W))
+
+
 @pytest.mark.parametrize("config,layers", [(1, 2), (2, 4), (3, 2), (4, 1), (5, 1)])
 def test_acceptance_full_size(config, layers):
     cfg = wl.CONFIGS[config]
