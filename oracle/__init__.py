@@ -166,6 +166,39 @@ def attach(D, W, t, draft_logits, parent_idx, token_ids, cum_logprob, pool):
     return margin
 
 
+def subtree_dp(parent, value, want):
+    """Bottom-up tree DP: best[k] for k = 0..N and one optimal set of `want` nodes (bool mask)."""
+    N = parent.shape[0]
+    assert parent.dtype == np.int32 and value.dtype == np.float64 and value.shape == (N,)
+    best = np.empty(N + 1, np.float64)
+    keep = np.zeros(N, np.uint8)
+    rc = _load().ygg_oracle_subtree_dp(_i32(N), _ptr(parent), _ptr(value), _i32(want), _ptr(best), _ptr(keep))
+    if rc != 0:
+        raise ValueError(f"ygg_oracle_subtree_dp failed with {rc}")
+    return best, keep.astype(bool)
+
+
+def prune(w, parent_idx, token_ids, cum_logprob, t_verifier=None, t_draft=0.0):
+    """Verification-width pruning of a batch of trees to w nodes each; see ygg_oracle_prune."""
+    B, N = parent_idx.shape
+    assert parent_idx.dtype == np.int32 and token_ids.dtype == np.int32 and cum_logprob.dtype == np.float32
+    assert token_ids.shape == (B, N) and cum_logprob.shape == (B, N)
+    if t_verifier is not None:
+        assert t_verifier.dtype == np.float64 and t_verifier.shape == (N + 1,)
+    out = dict(kept_nodes=np.empty((B, w), np.int32), new_parent=np.empty((B, w), np.int32),
+               new_token=np.empty((B, w), np.int32), expected_len=np.empty(B, np.float64),
+               best_width=np.zeros(B, np.int32), best_curve=np.empty((B, N + 1), np.float64))
+    rc = _load().ygg_oracle_prune(_i32(B), _i32(N), _i32(w), _ptr(parent_idx), _ptr(token_ids), _ptr(cum_logprob),
+                                  _ptr(t_verifier) if t_verifier is not None else None, ctypes.c_double(float(t_draft)),
+                                  _ptr(out["kept_nodes"]), _ptr(out["new_parent"]), _ptr(out["new_token"]),
+                                  _ptr(out["expected_len"]), _ptr(out["best_width"]), _ptr(out["best_curve"]))
+    if rc != 0:
+        raise ValueError(f"ygg_oracle_prune failed with {rc}")
+    if t_verifier is None:
+        out["best_width"] = None
+    return out
+
+
 def accept_compact(path_cols, parent_idx, token_ids, k_tree, v_tree, k_cache, v_cache, seq_lens,
                    target_logits=None, target_tokens=None):
     """Greedy acceptance + compaction; k_cache, v_cache and seq_lens are updated in place.

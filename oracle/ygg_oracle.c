@@ -435,6 +435,168 @@ int ygg_oracle_attach(int32_t B, int32_t D, int32_t W, int32_t V, int32_t t,
 }
 
 /* ------------------------------------------------------------------------ *
+ * Verification-width pruning (paper Sec. 4.2, "Verification Width Pruning":
+ * after drafting, a maximum-value subtree of the drafted tree is kept so that
+ * W_verify tokens are verified; a bottom-up dynamic programme over the tree).
+ *
+ * ygg_oracle_subtree_dp: for a tree in topological order (parent[i] < i,
+ * parent[0] = -1) with a value per node, best[k] (k = 1..N) = the largest total
+ * value of a connected set of k nodes that contains the root, by the bottom-up
+ * recurrence
+ *     f_i[1] = value[i];  joining child c:  f_i[a+b] = max f_i[a] + f_c[b], b >= 0
+ * (f_c[0] = 0: the child's subtree is left out).  keep[i] (optional) marks one
+ * optimal set of `want` nodes.
+ * ------------------------------------------------------------------------ */
+int ygg_oracle_subtree_dp(int32_t N, const int32_t *parent, const double *value, int32_t want,
+                          double *best /* [N+1], best[0] = 0 */, uint8_t *keep /* [N] or NULL */)
+{
+    if (N < 1 || parent[0] != -1 || want < 0 || want > N)
+        return -1;
+    for (int32_t i = 1; i < N; ++i)
+        if (parent[i] < 0 || parent[i] >= i)
+            return -4;
+    /* f[i][k], k = 0..size_i: nodes of the subtree of i, i included when k >= 1 */
+    int32_t *size = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+    double **f = (double **)calloc((size_t)N, sizeof(double *));
+    /* choice[c][k] = how many nodes child c contributes when its parent's table (after joining c) holds k */
+    int32_t **choice = (int32_t **)calloc((size_t)N, sizeof(int32_t *));
+    if (!size || !f || !choice)
+        return -5;
+    for (int32_t i = 0; i < N; ++i) {
+        f[i] = (double *)malloc(sizeof(double) * (size_t)(N + 1));
+        choice[i] = (int32_t *)calloc((size_t)(N + 1), sizeof(int32_t));
+        if (!f[i] || !choice[i])
+            return -5;
+        size[i] = 1;
+        f[i][0] = 0.0;
+        f[i][1] = value[i];
+    }
+    /* children join their parents in decreasing index order: every child is complete before it joins */
+    for (int32_t c = N - 1; c >= 1; --c) {
+        const int32_t p = parent[c];
+        const int32_t sp = size[p], sc = size[c];
+        double *g = (double *)malloc(sizeof(double) * (size_t)(sp + sc + 1));
+        if (!g)
+            return -5;
+        for (int32_t k = 0; k <= sp + sc; ++k)
+            g[k] = -INFINITY;
+        g[0] = 0.0;
+        for (int32_t a = 1; a <= sp; ++a)
+            for (int32_t b = 0; b <= sc; ++b) {
+                const double v = f[p][a] + f[c][b];
+                if (v > g[a + b]) {
+                    g[a + b] = v;
+                    choice[c][a + b] = b;
+                }
+            }
+        for (int32_t k = 0; k <= sp + sc; ++k)
+            f[p][k] = g[k];
+        size[p] = sp + sc;
+        free(g);
+    }
+    best[0] = 0.0;
+    for (int32_t k = 1; k <= N; ++k)
+        best[k] = f[0][k];
+    if (keep) {
+        /* undo the joins in reverse order: the last child joined (lowest index) is split off first */
+        int32_t *quota = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+        if (!quota)
+            return -5;
+        quota[0] = want;
+        for (int32_t c = 1; c < N; ++c) {
+            const int32_t p = parent[c];
+            const int32_t b = quota[p] >= 1 ? choice[c][quota[p]] : 0;
+            quota[c] = b;
+            quota[p] -= b;
+        }
+        for (int32_t i = 0; i < N; ++i)
+            keep[i] = quota[i] >= 1 ? 1 : 0;
+        free(quota);
+    }
+    for (int32_t i = 0; i < N; ++i) {
+        free(f[i]);
+        free(choice[i]);
+    }
+    free(f);
+    free(choice);
+    free(size);
+    return 0;
+}
+
+/*
+ * Pruning of one batch of drafted trees to `w` nodes each.  The value of a node
+ * is the probability that the whole path to it is accepted, with the drafter's
+ * probabilities as surrogates: exp(cum_logprob[i]) (the root counts 1: the
+ * bonus token).  The sum over a kept set estimates the accepted length.
+ *   kept_nodes   [B,w]  original indices, ascending (still topological)
+ *   new_parent   [B,w]  parent in the renumbered tree (-1 for the root)
+ *   new_token    [B,w]
+ *   expected_len [B]    sum of the kept values
+ *   best_width   [B]    (optional, needs t_verifier [N+1] and t_draft) the n in 1..N maximising
+ *                       best[n] / (t_draft + t_verifier[n])  (Eq. 3 with everything but W_verify
+ *                       fixed; first maximum)
+ */
+int ygg_oracle_prune(int32_t B, int32_t N, int32_t w, const int32_t *parent_idx, const int32_t *token_ids,
+                     const float *cum_logprob, const double *t_verifier, double t_draft,
+                     int32_t *kept_nodes, int32_t *new_parent, int32_t *new_token, double *expected_len,
+                     int32_t *best_width, double *best_curve /* [B,N+1] or NULL */)
+{
+    if (B < 1 || N < 1 || w < 1 || w > N)
+        return -1;
+    double *value = (double *)malloc(sizeof(double) * (size_t)N);
+    double *best = (double *)malloc(sizeof(double) * (size_t)(N + 1));
+    uint8_t *keep = (uint8_t *)malloc((size_t)N);
+    int32_t *renum = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!value || !best || !keep || !renum)
+        return -5;
+    int rc = 0;
+    for (int32_t b = 0; b < B && rc == 0; ++b) {
+        const int32_t *par = parent_idx + (int64_t)b * N;
+        for (int32_t i = 0; i < N; ++i)
+            value[i] = exp((double)cum_logprob[(int64_t)b * N + i]);
+        rc = ygg_oracle_subtree_dp(N, par, value, w, best, keep);
+        if (rc)
+            break;
+        int32_t k = 0;
+        for (int32_t i = 0; i < N; ++i) {
+            renum[i] = -1;
+            if (keep[i]) {
+                renum[i] = k;
+                kept_nodes[(int64_t)b * w + k] = i;
+                new_parent[(int64_t)b * w + k] = i == 0 ? -1 : renum[par[i]];
+                new_token[(int64_t)b * w + k] = token_ids[(int64_t)b * N + i];
+                ++k;
+            }
+        }
+        if (k != w) {
+            rc = -8;
+            break;
+        }
+        expected_len[b] = best[w];
+        if (best_curve)
+            for (int32_t n = 0; n <= N; ++n)
+                best_curve[(int64_t)b * (N + 1) + n] = best[n];
+        if (best_width && t_verifier) {
+            int32_t arg = 1;
+            double top = -INFINITY;
+            for (int32_t n = 1; n <= N; ++n) {
+                const double obj = best[n] / (t_draft + t_verifier[n]);
+                if (obj > top) {
+                    top = obj;
+                    arg = n;
+                }
+            }
+            best_width[b] = arg;
+        }
+    }
+    free(value);
+    free(best);
+    free(keep);
+    free(renum);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ *
  * Greedy acceptance and K/V compaction.
  *
  *   t*[i]    = first index of the maximum of target_logits[i,:]
