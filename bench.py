@@ -183,13 +183,17 @@ def main():
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
 
     # ---------------- the three calls on their own (graph replays), with their algorithmic rates
-    def replay_us(fn, reps=20):
+    def replay_us(fn, reps=20, inner=10):
+        # `inner` back-to-back calls per graph, so that the gap between two graph launches is not billed to a short call
+        def many():
+            for _ in range(inner):
+                fn()
         if args.no_graph:
-            run = fn
+            run = many
         else:
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
-                fn()
+                many()
             run = g.replay
         for _ in range(3):
             run()
@@ -199,7 +203,7 @@ def main():
             run()
         a1.record()
         torch.cuda.synchronize()
-        return a0.elapsed_time(a1) * 1e3 / reps
+        return a0.elapsed_time(a1) * 1e3 / (reps * inner)
 
     def grow_all():
         for d in range(1, D + 1):
@@ -213,16 +217,28 @@ def main():
         ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
                                accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
 
+    w_keep = max(1, (3 * N) // 4)
+    p_kept = torch.zeros((B, w_keep), dtype=torch.int32, device=dev)
+    p_par, p_tok = torch.zeros_like(p_kept), torch.zeros_like(p_kept)
+    p_len = torch.zeros((B,), dtype=torch.float32, device=dev)
+    p_best = torch.zeros((B,), dtype=torch.int32, device=dev)
+    t_ver = torch.linspace(1.0, 2.0, N + 1, dtype=torch.float32, device=dev)
+
+    def prune_only():   # pruning of the tree the growth calls left in e_parent / e_token / e_cum
+        ygg.prune_for_verification(shape, w_keep, e_parent, e_token, e_cum, p_kept, p_par, p_tok, p_len, p_best,
+                                   t_verifier=t_ver, t_draft=1.0)
+
     ops = None
     if not args.attention_only:
         grow_us = replay_us(grow_all)
         acc_us = replay_us(accept_only)
-        att_us = replay_us(attention_pass)
+        att_us = replay_us(attention_pass, inner=1)
         grow_bytes = sum(int(x.numel()) * 4 for x in draft)           # every draft logit read once
         acc_bytes = int(target.numel()) * 4                            # every target logit read once
         ops = {"growth_us_per_draft_step": round(grow_us / D, 2), "growth_gbps": round(grow_bytes / (grow_us * 1e-6) / 1e9, 1),
                "accept_us_per_call": round(acc_us, 2), "accept_argmax_gbps": round(acc_bytes / (acc_us * 1e-6) / 1e9, 1),
-               "attention_us_per_layer": round(att_us / n_layers, 2)}
+               "attention_us_per_layer": round(att_us / n_layers, 2),
+               "prune_us_per_call": round(replay_us(prune_only), 2), "prune_keeps": w_keep}
 
     # ---------------- dominant kernel: same launches again with dispatch-bound events
     ygg.profile_begin(args.steps * n_layers)

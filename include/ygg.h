@@ -151,6 +151,36 @@ int32_t ygg_equal_growth_attach(const ygg_shape *shape, int32_t t, const float *
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Verification-width pruning (paper Sec. 4.2 "Verification Width Pruning": after drafting, the
+ * maximum-value subtree with W_verify nodes is kept for verification; Eq. 3 with every term but
+ * W_verify fixed decides the width).  The value of a node is the probability that its whole path is
+ * accepted with the drafter's probabilities as surrogates, exp(cum_logprob[i]) (the root counts 1:
+ * the bonus token); the sum over a kept set estimates the accepted length.
+ *
+ *   w_verify     HOST integer 1..N: the static width of the verifier pass that follows
+ *   parent_idx, token_ids [B,N] int32, cum_logprob [B,N] fp32: the drafted tree, with
+ *                cum_logprob[child] <= cum_logprob[parent] (true of sums of log-probabilities; the
+ *                kept set is the w_verify largest values, which is the optimal connected subtree
+ *                under exactly that condition)
+ *   t_verifier   [N+1] fp32 device, t_verifier[n] > 0 = verifier latency with n tokens; NULL if
+ *                best_width is NULL.  t_draft >= 0: total drafting latency, same unit (host scalar)
+ *   kept_nodes   [B,w_verify] int32 out: kept original indices, ascending (still topological)
+ *   new_parent   [B,w_verify] int32 out: parent in the renumbered tree (-1 for the root)
+ *   new_token    [B,w_verify] int32 out
+ *   expected_len [B] fp32 out or NULL: sum of the kept values
+ *   best_width   [B] int32 out or NULL: the n in 1..N maximising (sum of the n largest values) /
+ *                (t_draft + t_verifier[n]), first maximum -- a hint for the next step's width; it
+ *                stays on the device
+ * The renumbered tree feeds ygg_tree_attention / ygg_accept_and_compact with n_nodes = w_verify.
+ * Needs no workspace.
+ */
+int32_t ygg_prune_for_verification(const ygg_shape *shape, int32_t w_verify,
+                                   const int32_t *parent_idx, const int32_t *token_ids,
+                                   const float *cum_logprob, const float *t_verifier, float t_draft,
+                                   int32_t *kept_nodes, int32_t *new_parent, int32_t *new_token,
+                                   float *expected_len, int32_t *best_width, void *hip_stream);
+
+/*
  * Greedy acceptance and K/V compaction (paper Sec. 1: draft tokens that match the verifier's
  * own output are accepted; Sec. 5: the "accept speculation management" stage; Sec. 4.1 under
  * Eq. 2: the verifier's token after the last accepted one is the bonus token; Sec. 6: the

@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     load_library,
     profile_begin,
     profile_end,
+    prune_for_verification,
     status_string,
     tree_attention,
     workspace_bytes,

@@ -78,6 +78,8 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_attach_pool_bytes.argtypes = [shp]
         lib.ygg_equal_growth_attach.restype = i32
         lib.ygg_equal_growth_attach.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp, sz, vp]
+        lib.ygg_prune_for_verification.restype = i32
+        lib.ygg_prune_for_verification.argtypes = [shp, i32] + [vp] * 4 + [ctypes.c_float] + [vp] * 5 + [vp]
         lib.ygg_accept_and_compact.restype = i32
         lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
         lib.ygg_profile_begin.restype = i32
@@ -169,6 +171,20 @@ def equal_growth_attach(shape: Shape, t: int, draft_logits, parent_idx, token_id
         _dev(parent_idx, torch.int32, "parent_idx"), _dev(token_ids, torch.int32, "token_ids"),
         _dev(cum_logprob, torch.float32, "cum_logprob"), pp, pn, wsp, wsn, _stream())
     _check(rc, "ygg_equal_growth_attach")
+
+
+def prune_for_verification(shape: Shape, w_verify: int, parent_idx, token_ids, cum_logprob, kept_nodes, new_parent,
+                           new_token, expected_len=None, best_width=None, t_verifier=None, t_draft: float = 0.0):
+    """ygg_prune_for_verification: keeps the w_verify most valuable nodes as a renumbered tree."""
+    cs = shape.c()
+    i32t = torch.int32
+    rc = load_library().ygg_prune_for_verification(
+        ctypes.byref(cs), w_verify, _dev(parent_idx, i32t, "parent_idx"), _dev(token_ids, i32t, "token_ids"),
+        _dev(cum_logprob, torch.float32, "cum_logprob"), _dev(t_verifier, torch.float32, "t_verifier"),
+        ctypes.c_float(t_draft), _dev(kept_nodes, i32t, "kept_nodes"), _dev(new_parent, i32t, "new_parent"),
+        _dev(new_token, i32t, "new_token"), _dev(expected_len, torch.float32, "expected_len"),
+        _dev(best_width, i32t, "best_width"), _stream())
+    _check(rc, "ygg_prune_for_verification")
 
 
 def accept_and_compact(shape: Shape, n_layers: int, parent_idx, token_ids, k_tree, v_tree, k_cache, v_cache,

@@ -279,6 +279,23 @@ int32_t ygg_equal_growth_attach(const ygg_shape* s, int32_t t, const float* draf
     return launch_attach(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
 }
 
+int32_t ygg_prune_for_verification(const ygg_shape* s, int32_t w_verify, const int32_t* parent_idx,
+                                   const int32_t* token_ids, const float* cum_logprob, const float* t_verifier,
+                                   float t_draft, int32_t* kept_nodes, int32_t* new_parent, int32_t* new_token,
+                                   float* expected_len, int32_t* best_width, void* hip_stream) {
+    if (int32_t rc = check_shape(s, false, false)) return rc;
+    if (!parent_idx || !token_ids || !cum_logprob || !kept_nodes || !new_parent || !new_token) return YGG_ERR_NULL;
+    if (best_width && !t_verifier) return YGG_ERR_NULL;
+    if (w_verify < 1 || w_verify > s->n_nodes) return YGG_ERR_SHAPE;
+    if (!(t_draft >= 0.f)) return YGG_ERR_SHAPE;
+    PruneArgs a{};
+    a.parent_idx = parent_idx; a.token_ids = token_ids; a.cum_logprob = cum_logprob; a.t_verifier = t_verifier;
+    a.kept_nodes = kept_nodes; a.new_parent = new_parent; a.new_token = new_token;
+    a.expected_len = expected_len; a.best_width = best_width; a.t_draft = t_draft;
+    a.B = s->batch; a.N = s->n_nodes; a.w = w_verify;
+    return launch_prune(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
 int32_t ygg_accept_and_compact(const ygg_shape* s, int32_t n_layers, const float* target_logits,
                                const int32_t* target_tokens, const int32_t* parent_idx, const int32_t* token_ids,
                                const void* k_tree, const void* v_tree, void* k_cache, void* v_cache,

@@ -80,6 +80,22 @@ int64_t attach_pool_capacity(const ygg_shape& s);
 size_t attach_pool_bytes(const ygg_shape& s);
 hipError_t launch_attach(const ExpandArgs& a, hipStream_t st);
 
+// ---- verification-width pruning ------------------------------------------------------------------
+struct PruneArgs {
+    const int32_t* parent_idx;
+    const int32_t* token_ids;
+    const float* cum_logprob;
+    const float* t_verifier;   // [N+1] or null
+    int32_t* kept_nodes;
+    int32_t* new_parent;
+    int32_t* new_token;
+    float* expected_len;       // or null
+    int32_t* best_width;       // or null
+    float t_draft;
+    int32_t B, N, w;
+};
+hipError_t launch_prune(const PruneArgs& a, hipStream_t st);
+
 // ---- acceptance + compaction ------------------------------------------------------------------
 struct AcceptPlan {
     int32_t chunk, nchunk;

@@ -124,6 +124,24 @@ def test_attach_rejects_bad_arguments_on_the_host():
     assert ygg.workspace_bytes(s, ygg.OP_ATTACH) > ygg.workspace_bytes(s, ygg.OP_EXPAND)
 
 
+def test_prune_rejects_bad_arguments_on_the_host():
+    lib = ygg.load_library()
+
+    def call(shape, w, ins, t_ver, outs, extra, t_draft=1.0):
+        cs = shape.c()
+        return lib.ygg_prune_for_verification(ctypes.byref(cs), w, *[ctypes.c_void_p(p) for p in ins],
+                                              ctypes.c_void_p(t_ver), ctypes.c_float(t_draft),
+                                              *[ctypes.c_void_p(p) for p in outs + extra], None)
+    ins, outs = [FAKE] * 3, [FAKE] * 3
+    assert call(_shape(), 0, ins, FAKE, outs, [FAKE, FAKE]) == ERR_SHAPE      # width out of range
+    assert call(_shape(), 14, ins, FAKE, outs, [FAKE, FAKE]) == ERR_SHAPE
+    assert call(_shape(), 5, ins, FAKE, outs, [FAKE, FAKE], t_draft=-1.0) == ERR_SHAPE
+    assert call(_shape(), 5, [0] + ins[1:], FAKE, outs, [FAKE, FAKE]) == ERR_NULL
+    assert call(_shape(), 5, ins, FAKE, [0] + outs[1:], [FAKE, FAKE]) == ERR_NULL
+    assert call(_shape(), 5, ins, 0, outs, [FAKE, FAKE]) == ERR_NULL           # best_width wanted without a latency table
+    assert call(_shape(n_nodes=2000, depth=3, width=4), 5, ins, FAKE, outs, [FAKE, FAKE]) in (ERR_SHAPE, ERR_UNSUPPORTED)
+
+
 def test_accept_rejects_bad_arguments_on_the_host():
     lib = ygg.load_library()
 
