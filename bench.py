@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="time only the attention calls of a step")
+    ap.add_argument("--tree", default="", help="override the tree of the configuration: D,W (N = 1 + D*W nodes)")
+    ap.add_argument("--heads", default="", help="override the head counts of the configuration: Hq,Hkv")
     ap.add_argument("--growth", choices=["frontier", "attach"], default="frontier",
                     help="draft-step rule: children of the previous depth only (default, the metric's definition) "
                          "or free attachment anywhere in the partial tree")
@@ -76,6 +78,15 @@ def main():
     ygg.load_library()  # fails loudly if libygg.so is missing
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.config]
+    variant = ""
+    if args.tree:
+        d_, w_ = (int(x) for x in args.tree.split(","))
+        cfg = wl.scaled(cfg, depth=d_, width=w_)
+        variant += f" with tree {d_}x{w_}"
+    if args.heads:
+        hq_, hkv_ = (int(x) for x in args.heads.split(","))
+        cfg = wl.scaled(cfg, n_q_heads=hq_, n_kv_heads=hkv_)
+        variant += f" with heads {hq_}/{hkv_}"
     n_layers = args.layers or cfg.n_layers
     B, N, D, W, V = cfg.batch, cfg.n_nodes, cfg.depth, cfg.width, cfg.vocab
     Hkv, Dh, cap = cfg.n_kv_heads, cfg.head_dim, cfg.kv_capacity
@@ -254,7 +265,7 @@ def main():
     else:
         bound, peak, unit, ach = "hbm", HBM_PEAK_GBS, "GB/s", nbytes / (kern_us * 1e-6) / 1e9
     roofline = {"bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config), "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
+                "traffic": None if variant else MEASURED_TRAFFIC_BYTES.get(args.config), "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
                 "launches_timed": kern_n, "algorithmic_bytes": nbytes, "flops": flops,
                 "gbps": round(nbytes / (kern_us * 1e-6) / 1e9, 1), "tflops": round(flops / (kern_us * 1e-6) / 1e12, 2)}
 
@@ -313,7 +324,7 @@ def main():
         "value": round(ms_per_step * 1e3 / n_layers, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}] {cfg.name}", "batch": B, "q_heads": cfg.n_q_heads,
+        "config": {"workload": f"configs[{args.config - 1}] {cfg.name}{variant}", "batch": B, "q_heads": cfg.n_q_heads,
                    "kv_heads": Hkv, "head_dim": Dh, "prefix": cfg.prefix_len or list(cfg.prefix_range),
                    "tree": f"depth {D} x width {W} + root = {N} nodes", "vocab": V, "layers": n_layers,
                    "scope": "attention only" if args.attention_only else "full step"},

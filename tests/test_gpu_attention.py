@@ -61,6 +61,8 @@ BF16_CASES = [
     (1, 4, 1, 10, 15, [190], 190),          # R = 604
     (1, 8, 8, 6, 8, [1500], 1500),          # several key splits, partial last tile
     (3, 8, 2, 3, 4, [700, 0, 64], 700),     # several splits with an empty and a one-tile sequence
+    (1, 40, 40, 8, 8, [1024], 1024),        # 13B-shaped layer (40 heads) with the paper's best static tree, 8 x 8
+    (1, 40, 40, 16, 8, [333], 333),         # ... and its fixed baseline tree, 16 x 8 (R = 129)
 ]
 
 
