@@ -40,7 +40,7 @@ def attention_work(cfg, lens):
 
 # HBM bytes per launch of the attention main kernel (fetched + written), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs
 # scaled by a streaming kernel of known size; a benchmark run cannot collect counters itself, so the figures measured with
-# the commands recorded in profiles/attn_mfma_hbm_traffic.md are carried here, per BASELINE configuration.
+# the commands recorded in profiles/attn_mfma_hbm_traffic.md are carried here, per workload configuration.
 MEASURED_TRAFFIC_BYTES = {2: 26_450_227, 3: 37_865_267, 4: 177_698_509, 5: 329_497_497}
 
 
@@ -64,7 +64,7 @@ def main():
                     help="also run a plain 256 MiB streaming kernel, dst = 2*src (reference point for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (--gpus 1); sharding is described in DESIGN.md",
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the design notes say how the path would shard",
               file=sys.stderr)
         sys.exit(2)
 
