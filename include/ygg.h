@@ -24,7 +24,7 @@
  *     unsupported type, workspace too small, launch failure).  Data-dependent contract
  *     violations (parent_idx not topological, seq_lens[b] > max_seq_len, NaN logits) are
  *     undefined behaviour, except that no kernel reads or writes outside the buffers as
- *     described by ygg_shape.
+ *     described by ygg_shape; ygg_debug_validate reports them.
  *   - Tensors are dense, row-major, token-major: [.., token, head, head_dim].
  *   - Tree layout: node 0 is the root (the last confirmed token, whose K/V is not yet in the
  *     cache); parent_idx[b][0] = -1 and 0 <= parent_idx[b][i] < i.  For the expansion call the
@@ -209,6 +209,25 @@ int32_t ygg_accept_and_compact(const ygg_shape *shape, int32_t n_layers,
                                void *k_cache, void *v_cache, int32_t *seq_lens,
                                int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token,
                                void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Debug validator for the data-dependent part of the contract above (the paper's runtime keeps the
+ * tree-structure array, the KV lengths and the token ids in a TokenTree object, Sec. 6; the calls
+ * here trust them).  Writes one bit mask per sequence to flags[b] (device memory, [B] int32); every
+ * input may be NULL, its checks are then skipped.  Not on the verification path: call it while
+ * bringing a caller up, read the flags after synchronising.
+ *   parent_idx [B,N]: YGG_BAD_PARENT if parent_idx[b][0] != -1 or some parent_idx[b][i] not in
+ *                     [0, i); otherwise YGG_BAD_DEPTH if some node is deeper than `depth`
+ *   seq_lens   [B]:   YGG_BAD_SEQ_LEN if outside [0, max_seq_len]
+ *   token_ids  [B,N]: YGG_BAD_TOKEN if outside [0, vocab)
+ *   logits     [B,logit_rows,V] fp32: YGG_BAD_LOGIT if any entry is NaN
+ */
+typedef enum {
+    YGG_BAD_PARENT = 1, YGG_BAD_SEQ_LEN = 2, YGG_BAD_DEPTH = 4, YGG_BAD_TOKEN = 8, YGG_BAD_LOGIT = 16
+} ygg_violation;
+int32_t ygg_debug_validate(const ygg_shape *shape, const int32_t *parent_idx, const int32_t *seq_lens,
+                           const int32_t *token_ids, const float *logits, int32_t logit_rows,
+                           int32_t *flags, void *hip_stream);
 
 /*
  * Measurement hook for benchmarks (not part of the verification path; not thread-safe).

@@ -199,6 +199,25 @@ def prune(w, parent_idx, token_ids, cum_logprob, t_verifier=None, t_draft=0.0):
     return out
 
 
+def validate(depth, vocab, max_seq_len, parent_idx=None, seq_lens=None, token_ids=None, logits=None):
+    """Per-sequence violation flags of the data-dependent calling contract (see ygg_oracle_validate)."""
+    ref = next(a for a in (parent_idx, token_ids, seq_lens, logits) if a is not None)
+    B = ref.shape[0]
+    N = parent_idx.shape[1] if parent_idx is not None else (token_ids.shape[1] if token_ids is not None else 1)
+    rows = 0
+    if logits is not None:
+        assert logits.dtype == np.float32 and logits.ndim == 3 and logits.shape[2] == vocab
+        rows = logits.shape[1]
+    for a in (parent_idx, seq_lens, token_ids):
+        assert a is None or a.dtype == np.int32
+    flags = np.zeros(B, np.int32)
+    rc = _load().ygg_oracle_validate(_i32(B), _i32(N), _i32(depth), _i32(vocab), _i32(max_seq_len), _ptr(parent_idx),
+                                     _ptr(seq_lens), _ptr(token_ids), _ptr(logits), _i32(rows), _ptr(flags))
+    if rc != 0:
+        raise ValueError(f"ygg_oracle_validate failed with {rc}")
+    return flags
+
+
 def accept_compact(path_cols, parent_idx, token_ids, k_tree, v_tree, k_cache, v_cache, seq_lens,
                    target_logits=None, target_tokens=None):
     """Greedy acceptance + compaction; k_cache, v_cache and seq_lens are updated in place.

@@ -700,3 +700,57 @@ int ygg_oracle_accept_compact(int32_t B, int32_t N, int32_t V, int32_t path_cols
     free(match);
     return rc;
 }
+
+/* ------------------------------------------------------------------------ *
+ * Check of the data-dependent part of the calling contract (the device calls
+ * treat a violation as undefined behaviour).  flags[b] collects, per sequence:
+ *   1  parent_idx[b][0] != -1, or some parent_idx[b][i] outside [0, i)
+ *   2  seq_lens[b] outside [0, max_seq_len]
+ *   4  some node deeper than `depth` (only judged when the parents are valid)
+ *   8  some token_ids[b][i] outside [0, vocab)
+ *  16  a NaN among logits[b][*][*]
+ * Any of the arrays may be NULL: its checks are skipped.
+ * ------------------------------------------------------------------------ */
+int ygg_oracle_validate(int32_t B, int32_t N, int32_t depth, int32_t vocab, int32_t max_seq_len,
+                        const int32_t *parent_idx, const int32_t *seq_lens, const int32_t *token_ids,
+                        const float *logits, int32_t logit_rows, int32_t *flags)
+{
+    if (B < 1 || N < 1)
+        return -1;
+    int32_t *dep = (int32_t *)malloc(sizeof(int32_t) * (size_t)N);
+    if (!dep)
+        return -5;
+    for (int32_t b = 0; b < B; ++b) {
+        int32_t f = 0;
+        if (parent_idx) {
+            const int32_t *par = parent_idx + (int64_t)b * N;
+            int ok = par[0] == -1;
+            for (int32_t i = 1; i < N; ++i)
+                if (par[i] < 0 || par[i] >= i)
+                    ok = 0;
+            if (!ok) {
+                f |= 1;
+            } else {
+                dep[0] = 0;
+                for (int32_t i = 1; i < N; ++i) {
+                    dep[i] = dep[par[i]] + 1;
+                    if (dep[i] > depth)
+                        f |= 4;
+                }
+            }
+        }
+        if (seq_lens && (seq_lens[b] < 0 || seq_lens[b] > max_seq_len))
+            f |= 2;
+        if (token_ids)
+            for (int32_t i = 0; i < N; ++i)
+                if (token_ids[(int64_t)b * N + i] < 0 || token_ids[(int64_t)b * N + i] >= vocab)
+                    f |= 8;
+        if (logits)
+            for (int64_t e = 0; e < (int64_t)logit_rows * vocab; ++e)
+                if (isnan(logits[(int64_t)b * logit_rows * vocab + e]))
+                    f |= 16;
+        flags[b] = f;
+    }
+    free(dep);
+    return 0;
+}

@@ -80,6 +80,8 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_equal_growth_attach.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp, sz, vp]
         lib.ygg_prune_for_verification.restype = i32
         lib.ygg_prune_for_verification.argtypes = [shp, i32] + [vp] * 4 + [ctypes.c_float] + [vp] * 5 + [vp]
+        lib.ygg_debug_validate.restype = i32
+        lib.ygg_debug_validate.argtypes = [shp] + [vp] * 4 + [i32, vp, vp]
         lib.ygg_accept_and_compact.restype = i32
         lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
         lib.ygg_profile_begin.restype = i32
@@ -185,6 +187,17 @@ def prune_for_verification(shape: Shape, w_verify: int, parent_idx, token_ids, c
         _dev(new_token, i32t, "new_token"), _dev(expected_len, torch.float32, "expected_len"),
         _dev(best_width, i32t, "best_width"), _stream())
     _check(rc, "ygg_prune_for_verification")
+
+
+def debug_validate(shape: Shape, flags, parent_idx=None, seq_lens=None, token_ids=None, logits=None):
+    """ygg_debug_validate: per-sequence violation bit masks into `flags` ([B] int32 on the GPU)."""
+    cs = shape.c()
+    rows = 0 if logits is None else int(logits.shape[1])
+    rc = load_library().ygg_debug_validate(
+        ctypes.byref(cs), _dev(parent_idx, torch.int32, "parent_idx"), _dev(seq_lens, torch.int32, "seq_lens"),
+        _dev(token_ids, torch.int32, "token_ids"), _dev(logits, torch.float32, "logits"), rows,
+        _dev(flags, torch.int32, "flags"), _stream())
+    _check(rc, "ygg_debug_validate")
 
 
 def accept_and_compact(shape: Shape, n_layers: int, parent_idx, token_ids, k_tree, v_tree, k_cache, v_cache,

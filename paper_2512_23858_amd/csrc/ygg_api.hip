@@ -296,6 +296,20 @@ int32_t ygg_prune_for_verification(const ygg_shape* s, int32_t w_verify, const i
     return launch_prune(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
 }
 
+int32_t ygg_debug_validate(const ygg_shape* s, const int32_t* parent_idx, const int32_t* seq_lens,
+                           const int32_t* token_ids, const float* logits, int32_t logit_rows, int32_t* flags,
+                           void* hip_stream) {
+    if (int32_t rc = check_shape(s, false, token_ids != nullptr || logits != nullptr)) return rc;
+    if (!flags) return YGG_ERR_NULL;
+    if (logits && logit_rows < 1) return YGG_ERR_SHAPE;
+    if (s->batch > 65535) return YGG_ERR_UNSUPPORTED;
+    ValidateArgs a{};
+    a.parent_idx = parent_idx; a.seq_lens = seq_lens; a.token_ids = token_ids; a.logits = logits; a.flags = flags;
+    a.B = s->batch; a.N = s->n_nodes; a.D = s->depth; a.V = s->vocab; a.max_seq_len = s->max_seq_len;
+    a.logit_rows = logit_rows;
+    return launch_validate(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
 int32_t ygg_accept_and_compact(const ygg_shape* s, int32_t n_layers, const float* target_logits,
                                const int32_t* target_tokens, const int32_t* parent_idx, const int32_t* token_ids,
                                const void* k_tree, const void* v_tree, void* k_cache, void* v_cache,

@@ -96,6 +96,17 @@ struct PruneArgs {
 };
 hipError_t launch_prune(const PruneArgs& a, hipStream_t st);
 
+// ---- debug validator ------------------------------------------------------------------------------
+struct ValidateArgs {
+    const int32_t* parent_idx;
+    const int32_t* seq_lens;
+    const int32_t* token_ids;
+    const float* logits;
+    int32_t* flags;
+    int32_t B, N, D, V, max_seq_len, logit_rows;
+};
+hipError_t launch_validate(const ValidateArgs& a, hipStream_t st);
+
 // ---- acceptance + compaction ------------------------------------------------------------------
 struct AcceptPlan {
     int32_t chunk, nchunk;

@@ -142,6 +142,17 @@ def test_prune_rejects_bad_arguments_on_the_host():
     assert call(_shape(n_nodes=2000, depth=3, width=4), 5, ins, FAKE, outs, [FAKE, FAKE]) in (ERR_SHAPE, ERR_UNSUPPORTED)
 
 
+def test_validator_rejects_bad_arguments_on_the_host():
+    lib = ygg.load_library()
+    cs = _shape().c()
+    f = lambda flags, rows, logits: lib.ygg_debug_validate(ctypes.byref(cs), *[ctypes.c_void_p(FAKE)] * 3, ctypes.c_void_p(logits),
+                                                           rows, ctypes.c_void_p(flags), None)
+    assert f(0, 1, FAKE) == ERR_NULL
+    assert f(FAKE, 0, FAKE) == ERR_SHAPE      # logits without a row count
+    bad = _shape(n_nodes=0).c()
+    assert lib.ygg_debug_validate(ctypes.byref(bad), None, None, None, None, 0, ctypes.c_void_p(FAKE), None) == ERR_SHAPE
+
+
 def test_accept_rejects_bad_arguments_on_the_host():
     lib = ygg.load_library()
 

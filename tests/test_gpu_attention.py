@@ -63,6 +63,8 @@ BF16_CASES = [
     (3, 8, 2, 3, 4, [700, 0, 64], 700),     # several splits with an empty and a one-tile sequence
     (1, 40, 40, 8, 8, [1024], 1024),        # 13B-shaped layer (40 heads) with the paper's best static tree, 8 x 8
     (1, 40, 40, 16, 8, [333], 333),         # ... and its fixed baseline tree, 16 x 8 (R = 129)
+    (1, 2, 2, 33, 31, [100], 100),          # the largest tree, N = 1024: ancestor masks of 32 words per node
+    (1, 8, 1, 1023, 1, [40], 40),           # N = 1024 as one chain (depth 1023) under one kv head: R = 8192
 ]
 
 

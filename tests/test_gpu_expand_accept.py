@@ -145,3 +145,15 @@ def test_accept_general_tree_full_chain_and_root_only():
     assert ref["accept_len"][0] == N
     ref = _accept_both(cfg, chain, tok, 1, np.array([5]), tstar=np.full((1, N), 63, np.int32), depth=N - 1)
     assert ref["accept_len"][0] == 1
+
+
+def test_accept_largest_tree_fully_accepted_chain():
+    """N = 1024 nodes as one chain, every draft token right: 1024 rows move into the cache of every layer."""
+    N = 1024
+    cfg = _cfg(2, N - 1, 1, 2000)
+    chain = np.stack([wl.chain_tree(N), wl.chain_tree(N)])
+    tok = np.stack([np.arange(N), np.arange(N)[::-1]]).astype(np.int32)
+    full = np.concatenate([tok[:, 1:], [[7], [8]]], axis=1).astype(np.int32)
+    full[1, 500] = 1999                                   # sequence 1 stops after 501 nodes
+    ref = _accept_both(cfg, chain, tok, 2, np.array([3, 0]), tstar=full, depth=N - 1)
+    assert ref["accept_len"].tolist() == [N, 501] and ref["bonus_token"].tolist() == [7, 1999]
