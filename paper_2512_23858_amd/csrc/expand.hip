@@ -257,6 +257,11 @@ __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
     const ChunkStat* stats = static_cast<const ChunkStat*>(a.stats) + (int64_t)b * K;
     const Cand* cands = static_cast<const Cand*>(a.cands) + (int64_t)b * K * a.W;
 
+    // entries of chunk list q = p*nchunk + c: min(W, size of chunk c), known without touching memory
+    auto list_len = [&](int q) {
+        const int c = q % a.nchunk;
+        return min(a.W, min(a.V, (c + 1) * a.chunk) - c * a.chunk);
+    };
     // 1. chunk statistics -> per-row log-sum-exp (fixed summation order: deterministic)
     int cnt[LPT];
     Cand head[LPT];
@@ -267,11 +272,12 @@ __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
         head[u].val = -INFINITY;
         head[u].idx = 0;
         if (q < K) {
+            // a chunk is never empty, so its list has a head: both loads go out together
             const ChunkStat st = stats[q];
+            head[u] = cands[(int64_t)q * a.W];
             smax[q] = st.maxv;
             ssum[q] = st.sumexp;
-            cnt[u] = st.count;
-            if (st.count > 0) head[u] = cands[(int64_t)q * a.W];
+            cnt[u] = list_len(q);
         }
     }
     __syncthreads();
@@ -318,7 +324,7 @@ __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
     //    strongest entries then sit in different lanes and the per-wavefront thresholds are tight.
     //    Every thread fetches its (at most 16) entries in one batch of loads.
     __shared__ int sel_cnt[kMaxWidth];
-    if (tid < nsel) sel_cnt[tid] = min(a.W, stats[sel[tid]].count);
+    if (tid < nsel) sel_cnt[tid] = list_len((int)sel[tid]);
     __syncthreads();
     constexpr int EPT = kMaxWidth * kMaxWidth / 256;  // 16
     auto get = [&](int u) {
