@@ -320,8 +320,14 @@ def main():
                "accept_s": round(t_accept, 4)}
 
     rec = {
-        "metric": "verify-step us per layer (expand + tree attention + accept/compact, whole step / layers)",
-        "value": round(ms_per_step * 1e3 / n_layers, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps,
+        # the headline metric's first part is `value`; its second part (achieved HBM TB/s and MFMA % of the attention
+        # main kernel) is spelled out in the two fields after `unit` and in `roofline`
+        "metric": "verify-step µs per layer + achieved HBM TB/s and MFMA % for tree attention",
+        "value": round(ms_per_step * 1e3 / n_layers, 3), "unit": "µs/layer",
+        "value_definition": "one whole verification step (D growth calls + `layers` attention calls + accept/compact) divided by layers",
+        "attention_hbm_tb_s": round(nbytes / (kern_us * 1e-6) / 1e12, 3),
+        "attention_mfma_pct_of_bf16_dense_peak": None if cfg.dtype == "f32" else round(100 * flops / (kern_us * 1e-6) / (MFMA_BF16_PEAK_TFLOPS * 1e12), 2),
+        "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}] {cfg.name}{variant}", "batch": B, "q_heads": cfg.n_q_heads,
