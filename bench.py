@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--attention-only", action="store_true", help="time only the attention calls of a step")
     ap.add_argument("--tree", default="", help="override the tree of the configuration: D,W (N = 1 + D*W nodes)")
     ap.add_argument("--heads", default="", help="override the head counts of the configuration: Hq,Hkv")
+    ap.add_argument("--prefix", type=int, default=0, help="override the KV prefix length of the configuration (all sequences)")
+    ap.add_argument("--batch", type=int, default=0, help="override the number of sequences of the configuration")
     ap.add_argument("--growth", choices=["frontier", "attach"], default="frontier",
                     help="draft-step rule: children of the previous depth only (default, the metric's definition) "
                          "or free attachment anywhere in the partial tree")
@@ -87,6 +89,12 @@ def main():
         hq_, hkv_ = (int(x) for x in args.heads.split(","))
         cfg = wl.scaled(cfg, n_q_heads=hq_, n_kv_heads=hkv_)
         variant += f" with heads {hq_}/{hkv_}"
+    if args.prefix:
+        cfg = wl.scaled(cfg, prefix_len=args.prefix, prefix_range=())
+        variant += f" with prefix {args.prefix}"
+    if args.batch:
+        cfg = wl.scaled(cfg, batch=args.batch)
+        variant += f" with batch {args.batch}"
     n_layers = args.layers or cfg.n_layers
     B, N, D, W, V = cfg.batch, cfg.n_nodes, cfg.depth, cfg.width, cfg.vocab
     Hkv, Dh, cap = cfg.n_kv_heads, cfg.head_dim, cfg.kv_capacity
