@@ -82,11 +82,11 @@ AttnPlan plan_attention(const ygg_shape& s) {
         }
         const int rw = p.waves / p.kshares * p.rblocks * 32;
         p.row_tiles = (R + rw - 1) / rw;
-        // fill the 256 CUs once with eight wavefronts each (more splits only add partial-result traffic),
-        // at least two key tiles per split
+        // fill the 256 CUs once -- the tile buffers leave room for one workgroup per CU, and a second round of
+        // workgroups pays the start-up latency again while more splits add partial-result traffic --
+        // with at least two key tiles per split
         const int64_t per_split = (int64_t)s.batch * s.n_kv_heads * p.row_tiles;
-        const int64_t wgs_per_cu = p.waves >= 6 ? 1 : 8 / p.waves;
-        ns = 256 * wgs_per_cu / per_split;
+        ns = 256 / per_split;
         if (ns > tiles / 2) ns = tiles / 2;
         if (ns_forced) ns = ns_forced < tiles ? ns_forced : tiles;
     } else {
