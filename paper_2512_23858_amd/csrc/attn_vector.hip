@@ -162,14 +162,15 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     const int64_t r = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
     if (r >= rows) return;
     const int c = (threadIdx.x % TPR) * 4;
+    const int nsp = a.nsplit;
     float mstar = -INFINITY, lstar = 0.f;
     float o[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int s0 = 0; s0 < a.nsplit; s0 += GS) {
+    for (int s0 = 0; s0 < nsp; s0 += GS) {
         float2 ml[GS];
         float4 v[GS];
 #pragma unroll
         for (int u = 0; u < GS; ++u) {
-            const int s = min(s0 + u, a.nsplit - 1);  // the tail repeats the last split; its weight is dropped below
+            const int s = min(s0 + u, nsp - 1);  // the tail repeats the last split; its weight is dropped below
             ml[u] = *reinterpret_cast<const float2*>(a.part_ml + ((int64_t)s * rows + r) * 2);
             v[u] = *reinterpret_cast<const float4*>(a.part_o + ((int64_t)s * rows + r) * DH + c);
         }
@@ -184,10 +185,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
         mstar = mg;
 #pragma unroll
         for (int u = 0; u < GS; ++u) {
-            const float w = (s0 + u < a.nsplit && ml[u].x != -INFINITY) ? expf(ml[u].x - mstar) : 0.f;
-            lstar = fmaf(ml[u].y, w, lstar);
-            o[0] = fmaf(v[u].x, w, o[0]); o[1] = fmaf(v[u].y, w, o[1]);
-            o[2] = fmaf(v[u].z, w, o[2]); o[3] = fmaf(v[u].w, w, o[3]);
+            // an empty split wrote only its (m = -inf, l = 0) record: its O~ is whatever the workspace held
+            const bool live = s0 + u < nsp && ml[u].x != -INFINITY;
+            const float w = live ? expf(ml[u].x - mstar) : 0.f;
+            const float4 vv = live ? v[u] : make_float4(0.f, 0.f, 0.f, 0.f);
+            lstar = fmaf(live ? ml[u].y : 0.f, w, lstar);
+            o[0] = fmaf(vv.x, w, o[0]); o[1] = fmaf(vv.y, w, o[1]);
+            o[2] = fmaf(vv.z, w, o[2]); o[3] = fmaf(vv.w, w, o[3]);
         }
     }
     const float inv = 1.f / lstar;

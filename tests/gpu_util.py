@@ -32,20 +32,20 @@ def shape_of(cfg: wl.Config, max_seq_len=None, kv_capacity=None, n_nodes=None) -
         max_seq_len=cfg.max_prefix if max_seq_len is None else max_seq_len)
 
 
-def workspace(shape: ygg.Shape, op: int, n_layers: int = 0) -> torch.Tensor:
+def workspace(shape: ygg.Shape, op: int, n_layers: int = 0, poison: int = 0xA5) -> torch.Tensor:
     n = ygg.workspace_bytes(shape, op, n_layers)
     assert n > 0, "invalid shape for workspace query"
-    # poison the scratch space: kernels must not rely on its contents
-    return torch.full((n,), 0xA5, dtype=torch.uint8, device=DEV)
+    # poison the scratch space: kernels must not rely on its contents (0xFF bytes read as NaN)
+    return torch.full((n,), poison, dtype=torch.uint8, device=DEV)
 
 
-def run_attention(shape: ygg.Shape, host: dict, parent_idx: np.ndarray, want_lse=True):
+def run_attention(shape: ygg.Shape, host: dict, parent_idx: np.ndarray, want_lse=True, poison: int = 0xA5):
     """host: dict with q,k_cache,v_cache,k_tree,v_tree,seq_lens (numpy).  Returns (out f64, lse f64)."""
     d = {k: to_dev(np.ascontiguousarray(v)) for k, v in host.items()}
     par = to_dev(np.ascontiguousarray(parent_idx))
     out = torch.full_like(d["q"], float("nan"))
     lse = torch.full(d["q"].shape[:3], float("nan"), dtype=torch.float32, device=DEV) if want_lse else None
-    ws = workspace(shape, ygg.OP_ATTENTION)
+    ws = workspace(shape, ygg.OP_ATTENTION, poison=poison)
     ygg.tree_attention(shape, d["q"], d["k_cache"], d["v_cache"], d["seq_lens"], d["k_tree"], d["v_tree"], par,
                        out, lse, ws)
     torch.cuda.synchronize()

@@ -107,3 +107,17 @@ def test_fp32_shapes(case):
 def test_bf16_head_dim_64_uses_vector_path():
     cfg, host, parent = _inputs(_cfg(1, 4, 2, 3, 4, Dh=64, seed=95), [90], 90)
     _check(cfg, host, parent, 90)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_empty_key_splits_ignore_whatever_the_workspace_holds(dtype):
+    """A sequence much shorter than max_seq_len leaves key splits empty: their slots of the workspace are never
+    written and may hold NaN bit patterns, which the merge must not touch."""
+    cfg, host, parent = _inputs(_cfg(3, 8, 2, 3, 4, dtype=dtype, seed=96), [700, 0, 64], 700)
+    ref_out, ref_lse = oracle.tree_attention(host["q"], host["k_cache"], host["v_cache"], host["seq_lens"],
+                                             host["k_tree"], host["v_tree"], parent, cfg.softmax_scale)
+    shape = shape_of(cfg, max_seq_len=700)
+    out, lse = run_attention(shape, host, parent, poison=0xFF)
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    assert np.abs(out - ref_out).max() <= tol
