@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void compact_kernel(AcceptArgs a) {
     if (k >= a.accept_len[b]) return;
     const int node = a.accept_path[(int64_t)b * (a.D + 1) + k];
     const int64_t dst_tok = (int64_t)a.old_len[b] + k;
-    if (node < 0 || node >= a.N || dst_tok >= a.cap) return;
+    if (node < 0 || node >= a.N || dst_tok < 0 || dst_tok >= a.cap) return;  // contract violations stay inside the buffers
     const int64_t row16 = (int64_t)a.Hkv * a.Dh * a.elem_bytes / 16;  // 16-byte units per token row
     const int64_t src = (((int64_t)layer * a.B + b) * a.N + node) * row16;
     const int64_t dst = (((int64_t)layer * a.B + b) * a.cap + dst_tok) * row16;
