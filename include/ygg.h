@@ -20,6 +20,8 @@
  *     static-runtime property the paper asks of the drafting algorithm (Sec. 3, Sec. 4.2).
  *     The first call that uses a given kernel variant raises that kernel's dynamic shared-memory
  *     limit (a host-side function attribute): run every shape once eagerly before capturing it.
+ *     That bookkeeping is the library's only state; it is not synchronised, so the first calls of a
+ *     process should come from one thread.
  *   - The return code reports host-checkable errors only (null pointers, inconsistent shape,
  *     unsupported type, workspace too small, launch failure).  Data-dependent contract
  *     violations (parent_idx not topological, seq_lens[b] > max_seq_len, NaN logits) are
