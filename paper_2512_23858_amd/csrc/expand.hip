@@ -424,11 +424,12 @@ __global__ __launch_bounds__(256) void attach_rows_kernel(ExpandArgs a) {
     }
 }
 
-// One workgroup per sequence; dynamic LDS holds n2 (a power of two) entries.
-__global__ __launch_bounds__(256) void attach_pool_kernel(ExpandArgs a, int n2) {
+// One workgroup per sequence (256 to 1024 threads: one compare-exchange per thread and stage where possible, the sort
+// is a chain of barriers); dynamic LDS holds n2 (a power of two) entries.
+__global__ __launch_bounds__(1024) void attach_pool_kernel(ExpandArgs a, int n2) {
     extern __shared__ __align__(16) unsigned char raw_sort[];
     Entry* e = reinterpret_cast<Entry*>(raw_sort);
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, nthr = blockDim.x;
     const int b = blockIdx.x;
     unsigned char* pool_b = static_cast<unsigned char*>(a.pool) + (size_t)b * (kPoolHeader + (size_t)a.pool_cap * sizeof(Offer));
     int32_t* pool_count = reinterpret_cast<int32_t*>(pool_b);
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(256) void attach_pool_kernel(ExpandArgs a, int n2) 
     int n_old = a.d == 1 ? 0 : *pool_count;
     n_old = n_old < 0 ? 0 : min(n_old, min(a.pool_cap, a.W * (a.D - a.d + 1)));  // what the previous step may have left
     const int n_new = a.F * a.W;
-    for (int i = tid; i < n2; i += 256) {
+    for (int i = tid; i < n2; i += nthr) {
         Entry x = {0, kNone, 0};
         if (i < n_old + n_new) {
             const Offer o = i < n_old ? pool[i] : offers[i - n_old];
@@ -450,7 +451,7 @@ __global__ __launch_bounds__(256) void attach_pool_kernel(ExpandArgs a, int n2) 
     // bitonic sort, best first (larger key, then lower node*V + token); empty slots sink to the end
     for (int k = 2; k <= n2; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = tid; i < (n2 >> 1); i += 256) {
+            for (int i = tid; i < (n2 >> 1); i += nthr) {
                 const int lo = ((i & ~(j - 1)) << 1) | (i & (j - 1));
                 const int hi = lo | j;
                 const Entry x = e[lo], y = e[hi];
@@ -461,7 +462,7 @@ __global__ __launch_bounds__(256) void attach_pool_kernel(ExpandArgs a, int n2) 
         }
     const int base_new = 1 + (a.d - 1) * a.W;
     const int keep = min(a.W * (a.D - a.d), n_old + n_new - a.W);
-    for (int i = tid; i < a.W + keep; i += 256) {
+    for (int i = tid; i < a.W + keep; i += nthr) {
         const Entry x = e[i];
         const int node = (int)(x.tie / (uint32_t)a.V), token = (int)(x.tie % (uint32_t)a.V);
         const double score = double_of(x.key);
@@ -537,7 +538,8 @@ hipError_t launch_attach(const ExpandArgs& a, hipStream_t st) {
     const int n = a.F * a.W + (a.d == 1 ? 0 : a.W * (a.D - a.d + 1));
     int n2 = 2;
     while (n2 < n) n2 <<= 1;
-    hipLaunchKernelGGL(attach_pool_kernel, dim3((unsigned)a.B), block, (size_t)n2 * sizeof(Entry), st, a, n2);
+    const int pool_threads = n2 / 2 < 256 ? 256 : (n2 / 2 > 1024 ? 1024 : n2 / 2);
+    hipLaunchKernelGGL(attach_pool_kernel, dim3((unsigned)a.B), dim3(pool_threads), (size_t)n2 * sizeof(Entry), st, a, n2);
     return hipGetLastError();
 }
 
