@@ -458,8 +458,18 @@ __global__ __launch_bounds__(1024) void attach_pool_kernel(ExpandArgs a, int n2)
                 const bool down = (lo & k) == 0;
                 if (down ? beats(y, x) : beats(x, y)) { e[lo] = y; e[hi] = x; }
             }
-            __syncthreads();
+            // Pairs at distance <= 64 stay inside one 128-element block, and a block belongs to the same wavefront
+            // in every stage: two such stages in a row need no workgroup barrier (LDS accesses of one wavefront
+            // complete in order; the fence keeps the compiler from moving them).
+            const int j_next = j > 1 ? j >> 1 : k;   // first distance of the next k is k
+            if (j <= 64 && j_next <= 64) {
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            } else {
+                __syncthreads();
+            }
         }
+    __syncthreads();  // the sorted order is read by every wavefront
     const int base_new = 1 + (a.d - 1) * a.W;
     const int keep = min(a.W * (a.D - a.d), n_old + n_new - a.W);
     for (int i = tid; i < a.W + keep; i += nthr) {

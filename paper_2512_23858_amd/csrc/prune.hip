@@ -42,9 +42,19 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(PruneArgs a, int n2) {
                 const bool down = (lo & k) == 0;
                 if (down ? y > x : x > y) { key[lo] = y; key[hi] = x; }
             }
-            __syncthreads();
+            // Pairs at distance <= 64 stay inside one 128-element block, and a block belongs to the same wavefront
+            // in every stage: two such stages in a row need no workgroup barrier (LDS accesses of one wavefront
+            // complete in order; the fence keeps the compiler from moving them).
+            const int j_next = j > 1 ? j >> 1 : k;   // first distance of the next k is k
+            if (j <= 64 && j_next <= 64) {
+                __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+            } else {
+                __syncthreads();
+            }
         }
 
+    __syncthreads();  // the sorted order is read by every wavefront
     // kept flags by original index; sorted values for the prefix sums
     constexpr int PER = kMaxNodes / kThreads;  // 4 consecutive positions per thread
     double v[PER];
