@@ -44,6 +44,17 @@ def attention_work(cfg, lens):
 MEASURED_TRAFFIC_BYTES = {2: 26_450_227, 3: 37_865_267, 4: 177_698_509, 5: 329_497_497}
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,6 +211,15 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    # the same K steps once more, each between its own pair of events: the median over steps, beside the mean above
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
+        body()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    ms_per_step_median = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
 
     # ---------------- the three calls on their own (graph replays), with their algorithmic rates
     def replay_us(fn, reps=20, inner=10):
@@ -275,6 +295,8 @@ def main():
     roofline = {"bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
                 "traffic": None if variant else MEASURED_TRAFFIC_BYTES.get(args.config), "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
                 "launches_timed": kern_n, "algorithmic_bytes": nbytes, "flops": flops,
+                "frac_of_hbm_peak": round(nbytes / (kern_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                "frac_of_mfma_bf16_peak": None if cfg.dtype == "f32" else round(flops / (kern_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                 "gbps": round(nbytes / (kern_us * 1e-6) / 1e9, 1), "tflops": round(flops / (kern_us * 1e-6) / 1e12, 2)}
 
     # ---------------- CPU oracle on a bounded sample of the same workload
@@ -321,7 +343,7 @@ def main():
             cpu_step = n_layers * t_attn_layer
         else:
             cpu_step = t_expand + n_layers * t_attn_layer + t_accept
-        cpu = {"value": round(cpu_step / n_layers * 1e6, 1), "unit": "us/layer", "cores": threads, "kind": "oracle",
+        cpu = {"value": round(cpu_step / n_layers * 1e6, 1), "unit": "us/layer", "cores": threads, "cpu_model": cpu_model(), "kind": "oracle",
                "sample": f"{attn_note}; expansion: all {D} steps; acceptance: argmax+match+1-layer compaction; "
                          f"step = expand + {n_layers} x attention layer + accept",
                "attention_layer_s": round(t_attn_layer, 4), "expand_s": round(t_expand, 4),
@@ -336,7 +358,7 @@ def main():
         "attention_hbm_tb_s": round(nbytes / (kern_us * 1e-6) / 1e12, 3),
         "attention_mfma_pct_of_bf16_dense_peak": None if cfg.dtype == "f32" else round(100 * flops / (kern_us * 1e-6) / (MFMA_BF16_PEAK_TFLOPS * 1e12), 2),
         "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": False, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "ms_per_step_median": round(ms_per_step_median, 5), "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"configs[{args.config - 1}] {cfg.name}{variant}", "batch": B, "q_heads": cfg.n_q_heads,
                    "kv_heads": Hkv, "head_dim": Dh, "prefix": cfg.prefix_len or list(cfg.prefix_range),
