@@ -232,6 +232,14 @@ int32_t ygg_debug_validate(const ygg_shape *shape, const int32_t *parent_idx, co
                            int32_t *flags, void *hip_stream);
 
 /*
+ * The launch plan ygg_tree_attention uses for a shape, for tests and tuning (host only, no GPU needed):
+ * plan[0] = 1 matrix-core kernel / 0 vector kernel, plan[1] = wavefronts per workgroup, plan[2] = 2 if
+ * wavefront pairs split every key tile else 1, plan[3] = workgroups along the query rows of one kv head,
+ * plan[4] = key splits (the last three are 0 / meaningless for the vector kernel except plan[4]).
+ */
+int32_t ygg_debug_attention_plan(const ygg_shape *shape, int32_t *plan /* [5], host */);
+
+/*
  * Measurement hook for benchmarks (not part of the verification path; not thread-safe).
  * Between ygg_profile_begin and ygg_profile_end every launch of the tree-attention main kernel
  * is bracketed by a pair of HIP events bound to that dispatch (hipExtLaunchKernelGGL), so the

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     Shape,
     accept_and_compact,
     attach_pool_bytes,
+    attention_plan,
     debug_validate,
     equal_growth_attach,
     equal_growth_expand,

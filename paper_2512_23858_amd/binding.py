@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_debug_validate.argtypes = [shp] + [vp] * 4 + [i32, vp, vp]
         lib.ygg_accept_and_compact.restype = i32
         lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
+        lib.ygg_debug_attention_plan.restype = i32
+        lib.ygg_debug_attention_plan.argtypes = [shp, ctypes.POINTER(i32)]
         lib.ygg_profile_begin.restype = i32
         lib.ygg_profile_begin.argtypes = [i32]
         lib.ygg_profile_end.restype = i32
@@ -215,6 +217,14 @@ def accept_and_compact(shape: Shape, n_layers: int, parent_idx, token_ids, k_tre
         _dev(accept_len, torch.int32, "accept_len"), _dev(accept_path, torch.int32, "accept_path"),
         _dev(bonus_token, torch.int32, "bonus_token"), wsp, wsn, _stream())
     _check(rc, "ygg_accept_and_compact")
+
+
+def attention_plan(shape: Shape) -> dict:
+    """ygg_debug_attention_plan: the launch plan of tree_attention for this shape (host only)."""
+    cs = shape.c()
+    out = (ctypes.c_int32 * 5)()
+    _check(load_library().ygg_debug_attention_plan(ctypes.byref(cs), out), "ygg_debug_attention_plan")
+    return dict(matrix_cores=bool(out[0]), waves=out[1], key_shares=out[2], row_tiles=out[3], key_splits=out[4])
 
 
 def profile_begin(max_launches: int):

@@ -119,6 +119,14 @@ using namespace ygg;
 
 extern "C" {
 
+int32_t ygg_debug_attention_plan(const ygg_shape* s, int32_t* plan) {
+    if (int32_t rc = check_shape(s, true, false)) return rc;
+    if (!plan) return YGG_ERR_NULL;
+    const AttnPlan p = plan_attention(*s);
+    plan[0] = p.use_mfma; plan[1] = p.waves; plan[2] = p.kshares; plan[3] = p.row_tiles; plan[4] = p.nsplit;
+    return YGG_OK;
+}
+
 int32_t ygg_profile_begin(int32_t max_launches) {
     if (max_launches < 1 || g_profile.on) return YGG_ERR_SHAPE;
     g_profile.start.resize((size_t)max_launches);

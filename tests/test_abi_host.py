@@ -176,3 +176,28 @@ def test_shape_struct_layout_matches_header():
     # 10 x int32/float (4 bytes each) + padding to 8 + int64 + int32 + tail padding
     assert ctypes.sizeof(_CShape) == 56
     assert _CShape.kv_capacity.offset == 40 and _CShape.max_seq_len.offset == 48
+
+
+def test_attention_plans_of_the_five_configurations(monkeypatch):
+    """The launch shapes the measurements were taken with (a change here is a performance change)."""
+    import ygg_workloads as wl
+    monkeypatch.delenv("YGG_ATTN_PLAN", raising=False)
+    want = {1: dict(matrix_cores=False),
+            2: dict(matrix_cores=True, waves=4, key_shares=2, row_tiles=1, key_splits=6),
+            3: dict(matrix_cores=True, waves=8, key_shares=2, row_tiles=5, key_splits=6),
+            4: dict(matrix_cores=True, waves=8, key_shares=1, row_tiles=6, key_splits=5),
+            5: dict(matrix_cores=True, waves=8, key_shares=1, row_tiles=2, key_splits=1)}
+    for c, exp in want.items():
+        cfg = wl.CONFIGS[c]
+        s = ygg.Shape(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                      depth=cfg.depth, width=cfg.width, n_nodes=cfg.n_nodes, vocab=cfg.vocab,
+                      kv_dtype=0 if cfg.dtype == "f32" else 1, softmax_scale=cfg.softmax_scale,
+                      kv_capacity=cfg.kv_capacity, max_seq_len=cfg.max_prefix)
+        got = ygg.attention_plan(s)
+        for k, v in exp.items():
+            assert got[k] == v, (c, k, got)
+    # the workspace follows the plan: one (Dh + 2)-float record per split and query row
+    s2 = _shape(max_seq_len=4096, kv_capacity=4200)
+    p = ygg.attention_plan(s2)
+    rows = s2.batch * s2.n_nodes * s2.n_q_heads
+    assert ygg.workspace_bytes(s2, ygg.OP_ATTENTION) >= p["key_splits"] * rows * 130 * 4
