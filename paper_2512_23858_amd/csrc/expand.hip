@@ -438,15 +438,29 @@ __global__ __launch_bounds__(1024) void attach_pool_kernel(ExpandArgs a, int n2)
     int n_old = a.d == 1 ? 0 : *pool_count;
     n_old = n_old < 0 ? 0 : min(n_old, min(a.pool_cap, a.W * (a.D - a.d + 1)));  // what the previous step may have left
     const int n_new = a.F * a.W;
-    for (int i = tid; i < n2; i += nthr) {
-        Entry x = {0, kNone, 0};
-        if (i < n_old + n_new) {
-            const Offer o = i < n_old ? pool[i] : offers[i - n_old];
-            x.key = key_of(o.score);
-            x.tie = (uint32_t)o.node * (uint32_t)a.V + (uint32_t)o.token;
-        }
-        e[i] = x;
+    // Only W*(D-t+1) entries are ever needed: the W new nodes and the pool kept for later.  When the carried pool
+    // alone already holds that many, an offer scoring below the pool's last entry cannot be among them, so it is
+    // dropped before the sort (exact: equal scores are kept), and the sort runs over what is left.
+    __shared__ int n_live;
+    const int need = a.W * (a.D - a.d + 1);
+    const uint64_t floor_key = (n_old >= need && n_old > 0) ? key_of(pool[n_old - 1].score) : 0ull;
+    if (tid == 0) n_live = n_old;
+    __syncthreads();
+    for (int i = tid; i < n_old + n_new; i += nthr) {
+        const Offer o = i < n_old ? pool[i] : offers[i - n_old];
+        Entry x;
+        x.key = key_of(o.score);
+        x.tie = (uint32_t)o.node * (uint32_t)a.V + (uint32_t)o.token;
+        x.tag = 0;
+        if (i < n_old) e[i] = x;
+        else if (x.key >= floor_key) e[atomicAdd(&n_live, 1)] = x;   // order before the sort does not matter
     }
+    __syncthreads();
+    const int n_sort = n_live;
+    int m2 = 2;
+    while (m2 < n_sort) m2 <<= 1;   // <= n2: the launch sized the buffer for every offer surviving
+    n2 = m2;
+    for (int i = n_sort + tid; i < n2; i += nthr) e[i] = Entry{0, kNone, 0};
     __syncthreads();
     // bitonic sort, best first (larger key, then lower node*V + token); empty slots sink to the end
     for (int k = 2; k <= n2; k <<= 1)
@@ -471,7 +485,7 @@ __global__ __launch_bounds__(1024) void attach_pool_kernel(ExpandArgs a, int n2)
         }
     __syncthreads();  // the sorted order is read by every wavefront
     const int base_new = 1 + (a.d - 1) * a.W;
-    const int keep = min(a.W * (a.D - a.d), n_old + n_new - a.W);
+    const int keep = min(a.W * (a.D - a.d), n_sort - a.W);
     for (int i = tid; i < a.W + keep; i += nthr) {
         const Entry x = e[i];
         const int node = (int)(x.tie / (uint32_t)a.V), token = (int)(x.tie % (uint32_t)a.V);
