@@ -309,6 +309,7 @@ __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
         hd[u] = Entry{0, kNone, 0};
         if (q < K && cnt[u] > 0) hd[u] = entry_of((uint32_t)q, head[u]);
     }
+    if (tid < kMaxWidth) sel[tid] = 0;  // every slot names a real list even if the ranks below were not a permutation
     wave_top_w<LPT>([&](int u) { return hd[u]; }, a.W, wave, lane, sh);
     __syncthreads();
     {
