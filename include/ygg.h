@@ -9,6 +9,10 @@
  *   ygg_accept_and_compact    acceptance of the matching draft path (Sec. 1, Sec. 5) and the
  *                             TokenTree's K/V bookkeeping (Sec. 6), done on the device
  *
+ * Around them: ygg_equal_growth_attach (the same draft step with free attachment, Sec. 4.2),
+ * ygg_prune_for_verification (verification-width pruning, Sec. 4.2), and ygg_debug_validate, which
+ * reports the data-dependent contract violations that the three calls above do not check.
+ *
  * Conventions shared by every call
  *   - All tensor pointers are DEVICE pointers owned by the caller; the ygg_shape struct is HOST
  *     memory and is only read during the call.  The library never allocates, frees or keeps
