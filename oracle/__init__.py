@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "ygg_oracle.c")
 _LIB = os.path.join(_HERE, "libygg_oracle.so")
 
-F32, BF16 = 0, 1
+F32, BF16, FP8_E4M3 = 0, 1, 2
 
 
 def build(force: bool = False) -> str:
@@ -42,6 +42,9 @@ def _load():
         for name in (
             "ygg_oracle_attention_row",
             "ygg_oracle_tree_attention",
+            "ygg_oracle_attention_row_fp8kv",
+            "ygg_oracle_tree_attention_fp8kv",
+            "ygg_oracle_fp8_e4m3_decode",
             "ygg_oracle_expand_scores",
             "ygg_oracle_expand",
             "ygg_oracle_accept_compact",
@@ -55,7 +58,9 @@ def _dtype_code(a: np.ndarray) -> int:
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError(f"expected float32 or uint16 (bf16 bits), got {a.dtype}")
+    if a.dtype == np.uint8:
+        return FP8_E4M3
+    raise TypeError(f"expected float32, uint16 (bf16 bits) or uint8 (E4M3 codes), got {a.dtype}")
 
 
 def _ptr(a):
@@ -96,6 +101,62 @@ def attention_row(q, k_cache, v_cache, seq_lens, k_tree, v_tree, parent_idx, sca
     if rc != 0:
         raise ValueError(f"ygg_oracle_attention_row failed with {rc}")
     return out, lse.value, probs
+
+
+def fp8_e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    """Values of E4M3 codes (uint8) as float64 (NaN for the two NaN codes)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    out = np.empty(codes.shape, np.float64)
+    rc = _load().ygg_oracle_fp8_e4m3_decode(_ptr(codes), ctypes.c_int64(codes.size), _ptr(out))
+    if rc != 0:
+        raise ValueError(f"ygg_oracle_fp8_e4m3_decode failed with {rc}")
+    return out
+
+
+def _attn_common_fp8kv(q, k_cache, v_cache, seq_lens, k_tree, v_tree, k_scale, v_scale, parent_idx):
+    B, N, Hq, Dh = q.shape
+    Bc, cap, Hkv, Dhc = k_cache.shape
+    assert (Bc, Dhc) == (B, Dh) and v_cache.shape == k_cache.shape
+    assert k_tree.shape == (B, N, Hkv, Dh) and v_tree.shape == k_tree.shape
+    assert parent_idx.shape == (B, N) and parent_idx.dtype == np.int32
+    assert seq_lens.shape == (B,) and seq_lens.dtype == np.int32
+    for a in (k_cache, v_cache, k_tree, v_tree):
+        assert a.dtype == np.uint8
+    for s in (k_scale, v_scale):
+        assert s.dtype == np.float32 and s.shape == (Hkv,)
+    return B, N, Hq, Hkv, Dh, cap, _dtype_code(q)
+
+
+def attention_row_fp8kv(q, k_cache, v_cache, seq_lens, k_tree, v_tree, k_scale, v_scale, parent_idx, scale,
+                        b, i, h):
+    """One output row with K/V stored as E4M3 codes and per-kv-head scales: (out[Dh], lse)."""
+    B, N, Hq, Hkv, Dh, cap, dt = _attn_common_fp8kv(q, k_cache, v_cache, seq_lens, k_tree, v_tree, k_scale,
+                                                    v_scale, parent_idx)
+    out = np.empty(Dh, np.float64)
+    lse = ctypes.c_double(0.0)
+    rc = _load().ygg_oracle_attention_row_fp8kv(
+        _i32(B), _i32(N), _i32(Hq), _i32(Hkv), _i32(Dh), ctypes.c_int(dt), ctypes.c_double(float(scale)),
+        ctypes.c_int64(cap), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(k_tree),
+        _ptr(v_tree), _ptr(k_scale), _ptr(v_scale), _ptr(parent_idx), _i32(b), _i32(i), _i32(h), _ptr(out),
+        ctypes.byref(lse), _ptr(None))
+    if rc != 0:
+        raise ValueError(f"ygg_oracle_attention_row_fp8kv failed with {rc}")
+    return out, lse.value
+
+
+def tree_attention_fp8kv(q, k_cache, v_cache, seq_lens, k_tree, v_tree, k_scale, v_scale, parent_idx, scale):
+    """All rows with K/V stored as E4M3 codes: (out[B,N,Hq,Dh] float64, lse[B,N,Hq] float64)."""
+    B, N, Hq, Hkv, Dh, cap, dt = _attn_common_fp8kv(q, k_cache, v_cache, seq_lens, k_tree, v_tree, k_scale,
+                                                    v_scale, parent_idx)
+    out = np.empty((B, N, Hq, Dh), np.float64)
+    lse = np.empty((B, N, Hq), np.float64)
+    rc = _load().ygg_oracle_tree_attention_fp8kv(
+        _i32(B), _i32(N), _i32(Hq), _i32(Hkv), _i32(Dh), ctypes.c_int(dt), ctypes.c_double(float(scale)),
+        ctypes.c_int64(cap), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(seq_lens), _ptr(k_tree),
+        _ptr(v_tree), _ptr(k_scale), _ptr(v_scale), _ptr(parent_idx), _ptr(out), _ptr(lse))
+    if rc != 0:
+        raise ValueError(f"ygg_oracle_tree_attention_fp8kv failed with {rc}")
+    return out, lse
 
 
 def tree_attention(q, k_cache, v_cache, seq_lens, k_tree, v_tree, parent_idx, scale):

@@ -29,7 +29,11 @@
  * L = 0), split/merge identity, brute-force top-W and path enumeration,
  * hand-worked fixtures under tests/golden/.
  *
- * Element types: 0 = fp32, 1 = bf16 (stored as uint16, upper half of an fp32).
+ * Element types: 0 = fp32, 1 = bf16 (stored as uint16, upper half of an fp32),
+ * 2 = 8-bit E4M3 codes (K and V of the *_fp8kv variants and of the compaction
+ * only; the paper does not fix the K/V precision, so this is a storage variant of
+ * the same definition: a stored element stands for its per-kv-head scale times
+ * the code's value).
  * All floating-point work is done in double.  Return value 0 = ok, negative =
  * invalid argument (see the checks at the top of each function).
  */
@@ -38,14 +42,43 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_FP8_E4M3 = 2 };
 
-static size_t elem_bytes(int dtype) { return dtype == ORC_F32 ? 4u : 2u; }
+static size_t elem_bytes(int dtype) { return dtype == ORC_F32 ? 4u : dtype == ORC_BF16 ? 2u : 1u; }
+
+/* 8-bit floating point, OCP E4M3: sign, 4 exponent bits (bias 7), 3 mantissa bits.
+ * Exponent field 0 holds the subnormals m/8 * 2^-6; there are no infinities; the
+ * all-ones exponent with all-ones mantissa is the only NaN; the largest finite
+ * value is 1.75 * 2^8 = 448. */
+static double fp8_e4m3_value(uint8_t code)
+{
+    const int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    double v;
+    if (e == 15 && m == 7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexp((double)m / 8.0, -6);
+    else
+        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/* out[i] = value of code[i]; exposed so that tests can pin the table */
+int ygg_oracle_fp8_e4m3_decode(const uint8_t *code, int64_t n, double *out)
+{
+    if (n < 0)
+        return -1;
+    for (int64_t i = 0; i < n; ++i)
+        out[i] = fp8_e4m3_value(code[i]);
+    return 0;
+}
 
 static double load_elem(const void *base, int dtype, int64_t idx)
 {
     if (dtype == ORC_F32)
         return (double)((const float *)base)[idx];
+    if (dtype == ORC_FP8_E4M3)
+        return fp8_e4m3_value(((const uint8_t *)base)[idx]);
     uint16_t h = ((const uint16_t *)base)[idx];
     uint32_t u = (uint32_t)h << 16;
     float f;
@@ -89,14 +122,16 @@ static int32_t node_depth(const int32_t *parent, int32_t i)
  * probs (optional, length L + N): p_j / l for prefix key j at [j] and for tree
  * node t at [L + t]; exactly 0.0 for nodes outside J(i).
  * ------------------------------------------------------------------------ */
-int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int32_t Dh,
-                             int dtype, double scale, int64_t cap,
-                             const void *q, const void *k_cache, const void *v_cache,
-                             const int32_t *seq_lens, const void *k_tree, const void *v_tree,
-                             const int32_t *parent_idx,
-                             int32_t b, int32_t i, int32_t h,
-                             double *out_row /* [Dh] */, double *lse /* [1] or NULL */,
-                             double *probs /* [L+N] or NULL */)
+static int attention_row_core(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int32_t Dh,
+                              int dtype /* of q */, int kv_dtype /* of K and V */,
+                              const float *k_scale, const float *v_scale /* [Hkv] or NULL = 1 */,
+                              double scale, int64_t cap,
+                              const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *seq_lens, const void *k_tree, const void *v_tree,
+                              const int32_t *parent_idx,
+                              int32_t b, int32_t i, int32_t h,
+                              double *out_row /* [Dh] */, double *lse /* [1] or NULL */,
+                              double *probs /* [L+N] or NULL */)
 {
     if (B < 1 || N < 1 || Hq < 1 || Hkv < 1 || Dh < 1 || Hq % Hkv != 0)
         return -1;
@@ -112,6 +147,9 @@ int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int3
     const int32_t G = Hq / Hkv;
     const int32_t hk = h / G;
     const int64_t q_off = (((int64_t)b * N + i) * Hq + h) * Dh;
+    /* a stored K (V) element stands for k_scale[hk] (v_scale[hk]) times its decoded value */
+    const double ks = k_scale ? (double)k_scale[hk] : 1.0;
+    const double vs = v_scale ? (double)v_scale[hk] : 1.0;
 
     char *visible = (char *)calloc((size_t)N, 1);
     double *s = (double *)malloc(sizeof(double) * (size_t)(L + N));
@@ -129,7 +167,7 @@ int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int3
         const int64_t k_off = (((int64_t)b * cap + j) * Hkv + hk) * Dh;
         double dot = 0.0;
         for (int32_t d = 0; d < Dh; ++d)
-            dot += load_elem(q, dtype, q_off + d) * load_elem(k_cache, dtype, k_off + d);
+            dot += load_elem(q, dtype, q_off + d) * (ks * load_elem(k_cache, kv_dtype, k_off + d));
         s[j] = scale * dot;
         if (s[j] > m)
             m = s[j];
@@ -140,7 +178,7 @@ int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int3
         const int64_t k_off = (((int64_t)b * N + t) * Hkv + hk) * Dh;
         double dot = 0.0;
         for (int32_t d = 0; d < Dh; ++d)
-            dot += load_elem(q, dtype, q_off + d) * load_elem(k_tree, dtype, k_off + d);
+            dot += load_elem(q, dtype, q_off + d) * (ks * load_elem(k_tree, kv_dtype, k_off + d));
         s[L + t] = scale * dot;
         if (s[L + t] > m)
             m = s[L + t];
@@ -168,7 +206,7 @@ int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int3
         const int64_t v_off = (((int64_t)b * cap + j) * Hkv + hk) * Dh;
         const double w = s[j] / l;
         for (int32_t d = 0; d < Dh; ++d)
-            out_row[d] += w * load_elem(v_cache, dtype, v_off + d);
+            out_row[d] += w * (vs * load_elem(v_cache, kv_dtype, v_off + d));
     }
     for (int32_t t = 0; t < N; ++t) {
         if (!visible[t])
@@ -176,7 +214,7 @@ int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int3
         const int64_t v_off = (((int64_t)b * N + t) * Hkv + hk) * Dh;
         const double w = s[L + t] / l;
         for (int32_t d = 0; d < Dh; ++d)
-            out_row[d] += w * load_elem(v_tree, dtype, v_off + d);
+            out_row[d] += w * (vs * load_elem(v_tree, kv_dtype, v_off + d));
     }
     if (lse)
         *lse = m + log(l);
@@ -187,6 +225,37 @@ int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int3
     free(visible);
     free(s);
     return 0;
+}
+
+int ygg_oracle_attention_row(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int32_t Dh,
+                             int dtype, double scale, int64_t cap,
+                             const void *q, const void *k_cache, const void *v_cache,
+                             const int32_t *seq_lens, const void *k_tree, const void *v_tree,
+                             const int32_t *parent_idx,
+                             int32_t b, int32_t i, int32_t h,
+                             double *out_row /* [Dh] */, double *lse /* [1] or NULL */,
+                             double *probs /* [L+N] or NULL */)
+{
+    return attention_row_core(B, N, Hq, Hkv, Dh, dtype, dtype, NULL, NULL, scale, cap, q, k_cache, v_cache,
+                              seq_lens, k_tree, v_tree, parent_idx, b, i, h, out_row, lse, probs);
+}
+
+/* The same row with K and V stored as E4M3 codes (one byte per element, same layouts) and one
+ * dequantisation factor per kv head: K = k_scale[hk] * value(code), V likewise.  q keeps `dtype`. */
+int ygg_oracle_attention_row_fp8kv(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int32_t Dh,
+                                   int dtype, double scale, int64_t cap,
+                                   const void *q, const uint8_t *k_cache, const uint8_t *v_cache,
+                                   const int32_t *seq_lens, const uint8_t *k_tree, const uint8_t *v_tree,
+                                   const float *k_scale, const float *v_scale,
+                                   const int32_t *parent_idx,
+                                   int32_t b, int32_t i, int32_t h,
+                                   double *out_row, double *lse, double *probs)
+{
+    if (!k_scale || !v_scale)
+        return -6;
+    return attention_row_core(B, N, Hq, Hkv, Dh, dtype, ORC_FP8_E4M3, k_scale, v_scale, scale, cap, q,
+                              k_cache, v_cache, seq_lens, k_tree, v_tree, parent_idx, b, i, h, out_row, lse,
+                              probs);
 }
 
 /* All rows: out [B,N,Hq,Dh] and lse [B,N,Hq] (lse may be NULL), in double. */
@@ -208,6 +277,33 @@ int ygg_oracle_tree_attention(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int
         int e = ygg_oracle_attention_row(B, N, Hq, Hkv, Dh, dtype, scale, cap, q, k_cache, v_cache,
                                          seq_lens, k_tree, v_tree, parent_idx, b, i, h,
                                          out + r * Dh, lse ? lse + r : NULL, NULL);
+        if (e != 0) {
+#pragma omp critical
+            rc = e;
+        }
+    }
+    return rc;
+}
+
+int ygg_oracle_tree_attention_fp8kv(int32_t B, int32_t N, int32_t Hq, int32_t Hkv, int32_t Dh,
+                                    int dtype, double scale, int64_t cap,
+                                    const void *q, const uint8_t *k_cache, const uint8_t *v_cache,
+                                    const int32_t *seq_lens, const uint8_t *k_tree, const uint8_t *v_tree,
+                                    const float *k_scale, const float *v_scale,
+                                    const int32_t *parent_idx, double *out, double *lse)
+{
+    if (B < 1 || N < 1 || Hq < 1 || Hkv < 1 || Dh < 1 || Hq % Hkv != 0)
+        return -1;
+    int rc = 0;
+    const int64_t rows = (int64_t)B * N * Hq;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t r = 0; r < rows; ++r) {
+        const int32_t h = (int32_t)(r % Hq);
+        const int32_t i = (int32_t)((r / Hq) % N);
+        const int32_t b = (int32_t)(r / ((int64_t)Hq * N));
+        int e = ygg_oracle_attention_row_fp8kv(B, N, Hq, Hkv, Dh, dtype, scale, cap, q, k_cache, v_cache,
+                                               seq_lens, k_tree, v_tree, k_scale, v_scale, parent_idx, b, i, h,
+                                               out + r * Dh, lse ? lse + r : NULL, NULL);
         if (e != 0) {
 #pragma omp critical
             rc = e;

@@ -91,6 +91,21 @@ def bf16_bits_to_f64(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
+def f64_to_fp8_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round to the 8-bit E4M3 format (4 exponent bits, bias 7, 3 mantissa bits, subnormals, no
+    infinities; round-to-nearest-even, magnitudes above 448 saturate), returned as uint8 codes."""
+    x = np.asarray(x, dtype=np.float64)
+    a = np.minimum(np.abs(x), 448.0)
+    _, ex = np.frexp(a)                                   # a = f * 2^ex, f in [0.5, 1)
+    e = np.maximum(ex - 1, -6)                            # exponent of the binade; subnormals share -6
+    r = np.rint(np.ldexp(a, 3 - e))                       # multiples of the binade's quantum 2^(e-3)
+    up = r >= 16                                          # rounded up into the next binade
+    e = np.where(up, e + 1, e)
+    r = np.where(up, 8.0, r)
+    code = np.where(r < 8, r, (e + 7) * 8 + (r - 8)).astype(np.uint8)   # r < 8 only for subnormals
+    return code | (np.signbit(x).astype(np.uint8) << np.uint8(7))
+
+
 def to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
     return x.astype(np.float32) if dtype == "f32" else f32_to_bf16_bits(x)
 
@@ -223,6 +238,25 @@ def attention_inputs(cfg: Config, layer: int = 0, lens: np.ndarray | None = None
         v_tree=normal(s, _S_VT, (B, N, Hkv, Dh), cfg.dtype),
         seq_lens=seq_lens(cfg) if lens is None else lens,
     )
+
+
+def attention_inputs_fp8kv(cfg: Config, layer: int = 0, lens: np.ndarray | None = None) -> dict:
+    """The same draws as attention_inputs with K and V stored as E4M3 codes: one scale per kv head
+    and tensor kind (K, V), chosen so that the head's largest magnitude over cache and tree maps to
+    448; code = round(x / scale).  Q keeps cfg.dtype."""
+    s = cfg.seed + layer
+    B, N, Hq, Hkv, Dh, cap = cfg.batch, cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.kv_capacity
+    out = dict(q=normal(s, _S_Q, (B, N, Hq, Dh), cfg.dtype), seq_lens=seq_lens(cfg) if lens is None else lens)
+    for name, sc, st in (("k", _S_KC, _S_KT), ("v", _S_VC, _S_VT)):
+        cache = normal(s, sc, (B, cap, Hkv, Dh), "f32")
+        tree = normal(s, st, (B, N, Hkv, Dh), "f32")
+        amax = np.maximum(np.abs(cache).max(axis=(0, 1, 3)), np.abs(tree).max(axis=(0, 1, 3)))
+        scale = (amax / np.float32(448.0)).astype(np.float32)
+        bc = scale.astype(np.float64)[None, None, :, None]
+        out[name + "_cache"] = f64_to_fp8_e4m3_bits(cache / bc)
+        out[name + "_tree"] = f64_to_fp8_e4m3_bits(tree / bc)
+        out[name + "_scale"] = scale
+    return out
 
 
 def expansion_inputs(cfg: Config, d: int) -> np.ndarray:
