@@ -57,7 +57,12 @@ typedef enum {
     YGG_ERR_LAUNCH = 5       /* the HIP runtime refused a launch */
 } ygg_status;
 
-typedef enum { YGG_F32 = 0, YGG_BF16 = 1 } ygg_dtype;
+typedef enum {
+    YGG_F32 = 0,
+    YGG_BF16 = 1,
+    YGG_FP8_E4M3 = 2   /* K and V (cache and tree) as 8-bit E4M3 codes, Q and O bf16; head_dim 128;
+                          accepted by ygg_tree_attention_fp8kv and ygg_accept_and_compact only */
+} ygg_dtype;
 
 typedef enum { YGG_OP_ATTENTION = 0, YGG_OP_EXPAND = 1, YGG_OP_ACCEPT = 2, YGG_OP_ATTACH = 3 } ygg_op;
 
@@ -70,7 +75,7 @@ typedef struct {
     int32_t width;         /* W: nodes added per draft step (1..64) */
     int32_t n_nodes;       /* N (1..1024); must equal 1 + D*W for ygg_equal_growth_expand */
     int32_t vocab;         /* V (only used by expand / accept) */
-    int32_t kv_dtype;      /* ygg_dtype of Q, K, V and O */
+    int32_t kv_dtype;      /* ygg_dtype of Q, K, V and O (see YGG_FP8_E4M3 for the mixed case) */
     float softmax_scale;   /* multiplies q.k; typically 1/sqrt(Dh) */
     int64_t kv_capacity;   /* token slots per sequence in the cache, >= max_seq_len + D + 1 */
     int32_t max_seq_len;   /* host-known upper bound of seq_lens[b] (sizes the launch grids) */
@@ -110,6 +115,28 @@ int32_t ygg_tree_attention(const ygg_shape *shape,
                            const int32_t *seq_lens, const void *k_tree, const void *v_tree,
                            const int32_t *parent_idx, void *out, float *lse,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The same attention with K and V stored in 8 bits (shape->kv_dtype == YGG_FP8_E4M3).  The paper
+ * leaves the K/V precision open (Sec. 6: the TokenTree owns the K/V tensors); this variant halves
+ * the bytes of the prefix, which is what bounds verification of small trees over long or batched
+ * prefixes.  A stored element is an E4M3 code (1 sign, 4 exponent bits with bias 7, 3 mantissa
+ * bits, subnormals, no infinities; codes 0x7f and 0xff are NaN and must not occur) and stands for
+ *     K = k_scale[g] * value(code),   V = v_scale[g] * value(code)        (g = kv head)
+ * The codes are widened to bf16 exactly, so the result is that of ygg_tree_attention on the
+ * dequantised K/V with the scales applied in fp32.
+ *
+ *   q, out     [B,N,Hq,Dh] bf16;  lse [B,N,Hq] fp32 or NULL
+ *   k_cache, v_cache [B,cap,Hkv,Dh] uint8;  k_tree, v_tree [B,N,Hkv,Dh] uint8
+ *   k_scale, v_scale [Hkv] fp32 device, finite and > 0
+ * Everything else as for ygg_tree_attention; workspace size is ygg_workspace_bytes(ATTENTION).
+ */
+int32_t ygg_tree_attention_fp8kv(const ygg_shape *shape,
+                                 const void *q, const void *k_cache, const void *v_cache,
+                                 const int32_t *seq_lens, const void *k_tree, const void *v_tree,
+                                 const float *k_scale, const float *v_scale,
+                                 const int32_t *parent_idx, void *out, float *lse,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * One draft step d (1..D) of the Equal-Growth Tree (paper Sec. 4.2 "Draft Width Selection":

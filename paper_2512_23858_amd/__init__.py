@@ -19,9 +19,13 @@ from .binding import (  # noqa: F401
     prune_for_verification,
     status_string,
     tree_attention,
+    tree_attention_fp8kv,
     workspace_bytes,
     OP_ATTENTION,
     OP_EXPAND,
     OP_ACCEPT,
     OP_ATTACH,
+    F32,
+    BF16,
+    FP8_E4M3,
 )

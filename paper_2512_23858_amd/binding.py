@@ -14,7 +14,7 @@ import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 OP_ATTENTION, OP_EXPAND, OP_ACCEPT, OP_ATTACH = 0, 1, 2, 3
-F32, BF16 = 0, 1
+F32, BF16, FP8_E4M3 = 0, 1, 2
 
 
 class _CShape(ctypes.Structure):
@@ -72,6 +72,8 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_status_string.argtypes = [i32]
         lib.ygg_tree_attention.restype = i32
         lib.ygg_tree_attention.argtypes = [shp] + [vp] * 9 + [vp, sz, vp]
+        lib.ygg_tree_attention_fp8kv.restype = i32
+        lib.ygg_tree_attention_fp8kv.argtypes = [shp] + [vp] * 11 + [vp, sz, vp]
         lib.ygg_equal_growth_expand.restype = i32
         lib.ygg_equal_growth_expand.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp]
         lib.ygg_attach_pool_bytes.restype = sz
@@ -125,7 +127,8 @@ def _check(rc: int, what: str):
 
 
 def _kv_torch_dtype(shape: Shape):
-    return torch.float32 if shape.kv_dtype == F32 else torch.bfloat16
+    """Element type of the K/V tensors (8-bit codes travel as uint8)."""
+    return {F32: torch.float32, BF16: torch.bfloat16, FP8_E4M3: torch.uint8}[shape.kv_dtype]
 
 
 def _ws(workspace):
@@ -146,6 +149,22 @@ def tree_attention(shape: Shape, q, k_cache, v_cache, seq_lens, k_tree, v_tree, 
         _dev(parent_idx, torch.int32, "parent_idx"), _dev(out, dt, "out"), _dev(lse, torch.float32, "lse"),
         wsp, wsn, _stream())
     _check(rc, "ygg_tree_attention")
+    return out
+
+
+def tree_attention_fp8kv(shape: Shape, q, k_cache, v_cache, seq_lens, k_tree, v_tree, k_scale, v_scale, parent_idx,
+                         out, lse=None, workspace=None):
+    """ygg_tree_attention_fp8kv: K/V as uint8 E4M3 codes with per-kv-head fp32 scales, Q and out bf16."""
+    cs = shape.c()
+    wsp, wsn = _ws(workspace)
+    u8, bf = torch.uint8, torch.bfloat16
+    rc = load_library().ygg_tree_attention_fp8kv(
+        ctypes.byref(cs), _dev(q, bf, "q"), _dev(k_cache, u8, "k_cache"), _dev(v_cache, u8, "v_cache"),
+        _dev(seq_lens, torch.int32, "seq_lens"), _dev(k_tree, u8, "k_tree"), _dev(v_tree, u8, "v_tree"),
+        _dev(k_scale, torch.float32, "k_scale"), _dev(v_scale, torch.float32, "v_scale"),
+        _dev(parent_idx, torch.int32, "parent_idx"), _dev(out, bf, "out"), _dev(lse, torch.float32, "lse"),
+        wsp, wsn, _stream())
+    _check(rc, "ygg_tree_attention_fp8kv")
     return out
 
 

@@ -35,6 +35,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int DH = 128;
 constexpr int ROWB = 256;  // bytes of one K or V row (head_dim 128, bf16) = 16 slots of 16 bytes
@@ -80,14 +81,58 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return (a >> 16) | (b & 0xffff0000u);
 }
 
+// Local-memory barrier: orders this wavefront's LDS traffic with the other wavefronts' without
+// waiting for its global loads in flight (a full workgroup fence would drain them).
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// 16-byte load from global memory proper (a pointer chosen between two arrays would otherwise be
+// loaded through the generic path, whose completion also counts as an LDS event).
+__device__ __forceinline__ u32x4 global_load16(uint64_t gaddr) {
+    return *reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(gaddr);
+}
+
+// Sixteen E4M3 codes (memory order) -> sixteen bf16; exact, the format has 3 mantissa bits.
+__device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& raw, uint4& first8, uint4& last8) {
+    const uint32_t w[4] = {raw[0], raw[1], raw[2], raw[3]};
+    uint32_t o[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], false);  // bytes 0, 1
+        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], true);   // bytes 2, 3
+        o[2 * i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
+        o[2 * i + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+    }
+    first8 = make_uint4(o[0], o[1], o[2], o[3]);
+    last8 = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
+template <int V>
+struct IntC {
+    static constexpr int value = V;
+};
+
 // NW wavefronts, RB 32-row blocks per wavefront, KT keys per tile, KS key shares: with KS = 2 the
 // wavefronts pair up on the same rows and each takes one of the two 32-key blocks of every tile (a
 // tree of few nodes has too few rows to occupy a workgroup otherwise); the pair's (m, l, O~) are
 // merged through LDS before the result is written.
-template <int NW, int RB, int KT, int KS>
-__global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
+//
+// KV8: K and V are stored as 8-bit E4M3 codes with one scale per kv head.  The codes are widened
+// to bf16 on their way into LDS (exactly), so tiles, operand reads and matrix work are those of
+// the bf16 kernel; the scales fold into the softmax scale and into the final normalisation.  The
+// direct-to-LDS path cannot convert, so the workgroup gets NLD extra wavefronts that do nothing but
+// load codes into registers (four tiles ahead), widen them and store the rows into the tile
+// buffers; the NW computing wavefronts never touch global K/V.  Both kinds meet at the same one
+// barrier per tile.
+template <int NW, int RB, int KT, int KS, bool KV8>
+__global__ __launch_bounds__((NW + (KV8 ? (NW < 4 ? NW : 4) : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
     static_assert(KS == 1 || (KS == 2 && NW % 2 == 0 && KT == 64), "key shares: one block of the tile each");
-    constexpr int THREADS = NW * 64;
+    constexpr int NLD = KV8 ? (NW < 4 ? NW : 4) : 0;             // loading wavefronts (KV8 only)
+    constexpr int THREADS = (NW + NLD) * 64;
+    static_assert(!KV8 || NW <= 4, "loading wavefronts share the SIMDs with at most one computing wavefront each");
     constexpr int NRW = NW / KS;                                 // wavefronts along the rows
     constexpr int RW = NRW * RB * 32;                            // query rows per workgroup
     constexpr int TILEB = KT * ROWB;                             // bytes of one K (or V) tile
@@ -103,7 +148,8 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform by construction
     const int n = lane & 31, g2 = lane >> 5;
-    const int wrow = KS == 1 ? wave : wave % NRW;  // position along the rows
+    const bool is_loader = KV8 && wave >= NW;      // wave-uniform
+    const int wrow = KS == 1 ? wave : wave % NRW;  // position along the rows (computing wavefronts)
     const int kh = KS == 1 ? 0 : wave / NRW;       // which block of every tile (KS = 2)
 
     // workgroup id -> (stream sigma = (b, kv head, split), row tile); sigma % 8 picks the XCD
@@ -136,7 +182,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
         const int i = min(row, R - 1) / a.G;
         const int g = min(row, R - 1) % a.G;
         node_of[rb] = i;
-        rg_of[rb] = row < R ? (b * a.N + i) * a.Hq + hk * a.G + g : -1;
+        rg_of[rb] = row < R && !is_loader ? (b * a.N + i) * a.Hq + hk * a.G + g : -1;
     }
 
     if (k0 >= k1) {  // empty split (uniform over the workgroup): mark the partials as absent
@@ -172,15 +218,16 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     int32_t* parent_s = reinterpret_cast<int32_t*>(anc_s + (i_last - i_first + 1) * aw);
 
     // slab bases of this (sequence, kv head): wave-uniform, pinned to scalar registers
-    auto uniform_ptr = [](const uint16_t* p) {
+    constexpr int EB = KV8 ? 1 : 2;  // bytes of a stored K/V element
+    auto uniform_ptr = [](const unsigned char* p) {
         const uint64_t v = (uint64_t)p;
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-        return reinterpret_cast<const uint16_t*>(((uint64_t)hi << 32) | lo);
+        return reinterpret_cast<const unsigned char*>(((uint64_t)hi << 32) | lo);
     };
-    const uint16_t* kc = uniform_ptr(static_cast<const uint16_t*>(a.k_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH);
-    const uint16_t* vc = uniform_ptr(static_cast<const uint16_t*>(a.v_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * DH);
-    const uint16_t* kt = uniform_ptr(static_cast<const uint16_t*>(a.k_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH);
-    const uint16_t* vt = uniform_ptr(static_cast<const uint16_t*>(a.v_tree) + ((int64_t)b * a.N * a.Hkv + hk) * DH);
+    const unsigned char* kc = uniform_ptr(static_cast<const unsigned char*>(a.k_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * (DH * EB));
+    const unsigned char* vc = uniform_ptr(static_cast<const unsigned char*>(a.v_cache) + ((int64_t)b * a.cap * a.Hkv + hk) * (DH * EB));
+    const unsigned char* kt = uniform_ptr(static_cast<const unsigned char*>(a.k_tree) + ((int64_t)b * a.N * a.Hkv + hk) * (DH * EB));
+    const unsigned char* vt = uniform_ptr(static_cast<const unsigned char*>(a.v_tree) + ((int64_t)b * a.N * a.Hkv + hk) * (DH * EB));
 
     // Direct-to-LDS tile fill: wave-instruction `inst` brings rows 4*inst .. 4*inst+3 of the tile;
     // lane l lands at byte 1024*inst + 16*l, i.e. row 4*inst + l/16, slot' = l%16, and therefore
@@ -191,7 +238,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     const uint32_t v_lds = (uint32_t)(size_t)(__attribute__((address_space(3))) void*)v_s;
     // Addresses are a wave-uniform 64-bit base (one sequence's K or V slab) plus a 32-bit byte offset;
     // the host checks that a slab stays below 4 GiB.
-    const uint32_t tok_bytes = (uint32_t)a.Hkv * DH * 2;
+    const uint32_t tok_bytes = (uint32_t)a.Hkv * DH * EB;
     // per-lane byte offsets of this wavefront's loads inside a tile of cache rows (fast path below)
     constexpr int FPW = (KT / 4) / FILLERS;  // wave-instructions per filling wavefront, tile and tensor
     uint32_t fill_k[FPW], fill_v[FPW];
@@ -244,6 +291,45 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
         }
     };
 
+    // KV8 loaders.  A tile is 16 wave-instructions of 16-byte loads: instruction g < 8 covers rows
+    // 8g .. 8g+7 of K, instruction 8 + g the same rows of V, eight lanes per row and sixteen codes per
+    // lane.  Loader lw takes instructions lw, lw + NLD, ... (NLD divides 8, so whether a load is K's or
+    // V's is known at compile time).  Rows past the end of the split repeat
+    // its last key, as above; every address is a cache row below L or a tree row below N whatever
+    // tile_base is, so a load may be issued for a tile that does not exist.
+    constexpr int LPT = 16 / (NLD > 0 ? NLD : 16);  // loads per loader and tile
+    struct Stage {
+        u32x4 d[LPT];
+    };
+    const int lw = wave - NW;
+    auto stage_issue = [&](Stage& sg, int tile_base) {
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            const bool is_v = it * NLD >= 8;  // known once the loop is unrolled
+            const int row = 8 * ((lw + it * NLD) & 7) + (lane >> 3);
+            const int j = min(tile_base + row, k1 - 1);
+            const bool in_cache = j < L;
+            const uint32_t off = (uint32_t)(in_cache ? j : j - L) * tok_bytes + 16 * (lane & 7);
+            const uint64_t base = is_v ? (in_cache ? (uint64_t)vc : (uint64_t)vt) : (in_cache ? (uint64_t)kc : (uint64_t)kt);
+            sg.d[it] = global_load16(base + off);
+        }
+    };
+    // widens the staged codes and stores them where the direct-to-LDS path would have put the bf16 row
+    auto stage_write = [&](const Stage& sg, int buf) {
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            const bool is_v = it * NLD >= 8;  // known once the loop is unrolled
+            const int row = 8 * ((lw + it * NLD) & 7) + (lane >> 3);
+            const int c2 = 2 * (lane & 7);  // this lane's two 16-byte slots: c2, c2 + 1
+            uint4 w0, w1;
+            e4m3x16_to_bf16(sg.d[it], w0, w1);
+            unsigned char* r = smem + (is_v ? NBUF * TILEB : 0) + buf * TILEB + row * ROWB;
+            const int x = is_v ? ((row & 3) << 2) : (row & 15);
+            *reinterpret_cast<uint4*>(r + 16 * (c2 ^ x)) = w0;
+            *reinterpret_cast<uint4*>(r + 16 * ((c2 + 1) ^ x)) = w1;
+        }
+    };
+
     f32x16 o[RB][4];
     float m_ref[RB], l_run[RB];
 #pragma unroll
@@ -253,7 +339,8 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
 #pragma unroll
         for (int db = 0; db < 4; ++db) o[rb][db] = f32x16{};
     }
-    const float c_scale = a.scale * kLog2e;
+    // KV8: K = k_scale * code value, so the scale (positive) joins the softmax scale
+    const float c_scale = a.scale * kLog2e * (KV8 ? a.k_scale[hk] : 1.f);
 
     // ---- the pipeline over 32-key blocks ---------------------------------------------------------
     // Each wavefront alternates between a vector phase (LDS operand reads issued, then the softmax
@@ -375,40 +462,102 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     static_assert(KT == 64, "the block pipeline below is written for two 32-key blocks per tile");
     const int ntiles = (k1 - k0 + KT - 1) / KT;
     const int clean_end = min(L, k1);
-    // prologue: up to three tiles go into flight at once; the ancestor masks are built meanwhile
-#pragma unroll
-    for (int i = 0; i < 3; ++i)
-        if (i < ntiles) fill_tile(i, k0 + i * KT);
-    if (has_tree_keys) {
+    auto build_masks = [&]() {  // every wavefront of the workgroup takes part
+        if (!has_tree_keys) return;
         // one coalesced read of parent_idx; the walks up the tree then stay in LDS
         const int32_t* parent = a.parent_idx + (int64_t)b * a.N;
         for (int t = tid; t < a.N; t += THREADS) parent_s[t] = parent[t];
-        __syncthreads();
+        if constexpr (KV8) lds_barrier(); else __syncthreads();
         for (int t = tid; t <= i_last - i_first; t += THREADS) {
             uint32_t* w = anc_s + t * aw;
             for (int x = 0; x < aw; ++x) w[x] = 0;
             int guard = 0;
             for (int c = i_first + t; c >= 0 && c < a.N && guard < a.N; c = parent_s[c], ++guard) w[c >> 5] |= 1u << (c & 31);
         }
-    }
-    constexpr int PT2 = 2 * PT > 63 ? 63 : 2 * PT;  // a single filling wavefront has 64 loads in flight: wait for one more
-    if (ntiles >= 3) dma_wait_keep<PT2>(); else if (ntiles == 2) dma_wait_keep<PT>(); else dma_wait_keep<0>();
-    __syncthreads();  // tile 0 has landed for everybody; anc_s published
+    };
 
-    // One barrier per tile: "tile t+1 has landed for everybody, and everybody is done with tile t-1's
-    // successor buffer", after which that buffer receives tile t+3.
+    // KV8, loading wavefronts.  Tile tau travels in register set tau & 3; iteration t (after the
+    // barrier that retires tile t) stores tile t+3 into tile t's buffer and reuses the set for the
+    // loads of tile t+7.  Every staged load is issued whether or not its tile exists: the number
+    // of loads in flight at each point is then the same on every path, and the compiler's wait for
+    // one register set leaves the three younger sets in flight.  The barriers match those of the
+    // computing wavefronts one for one.
+    if constexpr (KV8) {
+        if (is_loader) {
+            Stage stage[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) stage_issue(stage[i], k0 + i * KT);
+            build_masks();
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                stage_write(stage[i], i);
+                stage_issue(stage[i], k0 + (4 + i) * KT);
+            }
+            lds_barrier();  // tiles 0..2 are in LDS for everybody; anc_s published
+            int lbuf = 0;
+            auto lstep = [&](int t, Stage& sg) {
+                lds_barrier();
+                if (t + 3 < ntiles) stage_write(sg, lbuf);
+                stage_issue(sg, k0 + (t + 7) * KT);
+                lbuf = lbuf + 1 == NBUF ? 0 : lbuf + 1;
+            };
+            int t = 0;
+            for (; t + 3 < ntiles; t += 4) {
+                lstep(t, stage[3]);
+                lstep(t + 1, stage[0]);
+                lstep(t + 2, stage[1]);
+                lstep(t + 3, stage[2]);
+            }
+            if (t < ntiles) lstep(t, stage[3]);
+            if (t + 1 < ntiles) lstep(t + 1, stage[0]);
+            if (t + 2 < ntiles) lstep(t + 2, stage[1]);
+            if constexpr (KS == 2) {  // the merge of the key shares has two more workgroup barriers
+                __syncthreads();
+                __syncthreads();
+            }
+            return;
+        }
+    }
+
+    // prologue of the computing wavefronts: up to three tiles go into flight at once (direct-to-LDS
+    // path); the ancestor masks are built meanwhile
+    if constexpr (!KV8) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (i < ntiles) fill_tile(i, k0 + i * KT);
+    }
+    build_masks();
+    constexpr int PT2 = 2 * PT > 63 ? 63 : 2 * PT;  // a single filling wavefront has 64 loads in flight: wait for one more
+    if constexpr (KV8) {
+        lds_barrier();
+    } else {
+        if (ntiles >= 3) dma_wait_keep<PT2>(); else if (ntiles == 2) dma_wait_keep<PT>(); else dma_wait_keep<0>();
+        __syncthreads();  // tile 0 has landed for everybody; anc_s published
+    }
+
+    // After the barrier of iteration t every wavefront is done with tile t, whose buffer then receives
+    // tile t+3: by direct-to-LDS loads that the barrier of iteration t+2 awaits, or (KV8) from the loaders.
+    auto turn = [&](int t, int buf, int tile_base) {
+        if constexpr (KV8) {
+            lds_barrier();
+        } else {
+            if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();  // tile t+1 landed, t+2 may be in flight
+            __syncthreads();
+            if (t + 3 < ntiles) fill_tile(buf, tile_base + 3 * KT);  // tile t's buffer: every wavefront has read it
+        }
+    };
+
+    // One barrier per tile (inside turn).
     bf16x8 ka[8];
     i16x8 va[4][2];
     f32x16 st[RB];
     i16x8 pb[RB][2];
     int buf = 0;
-    if constexpr (KS == 1) {
-        read_k(0, 0, ka);
-        qk(ka, st);
-        for (int t = 0; t < ntiles; ++t) {
-            const int tile_base = k0 + t * KT;
-            const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
-            const bool clean = tile_base + KT <= clean_end;
+    auto body = [&](int t) {
+        const int tile_base = k0 + t * KT;
+        const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
+        const bool clean = tile_base + KT <= clean_end;
+        if constexpr (KS == 1) {
             // block 0 of the tile
             read_v(buf, 0, va);
             __builtin_amdgcn_sched_barrier(0);
@@ -422,36 +571,23 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
             read_v(buf, 1, va);
             __builtin_amdgcn_sched_barrier(0);
             softmax(st, pb, tile_base + 32, clean);
-            if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();  // tile t+1 landed, t+2 may be in flight
-            __syncthreads();
-            if (t + 3 < ntiles) fill_tile(buf, tile_base + 3 * KT);  // tile t's buffer: every wavefront has read it
-            if (t + 1 < ntiles) read_k(buf_next, 0, ka);
-            __builtin_amdgcn_sched_barrier(0);
-            pv(va, pb);
-            if (t + 1 < ntiles) qk(ka, st);
-            __builtin_amdgcn_sched_barrier(0);
-            buf = buf_next;
-        }
-    } else {
-        read_k(0, kh, ka);
-        qk(ka, st);
-        for (int t = 0; t < ntiles; ++t) {
-            const int tile_base = k0 + t * KT;
-            const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
-            const bool clean = tile_base + KT <= clean_end;
+        } else {
             read_v(buf, kh, va);
             __builtin_amdgcn_sched_barrier(0);
             softmax(st, pb, tile_base + 32 * kh, clean);
-            if (t + 2 < ntiles) dma_wait_keep<PT>(); else dma_wait_keep<0>();
-            __syncthreads();
-            if (t + 3 < ntiles) fill_tile(buf, tile_base + 3 * KT);
-            if (t + 1 < ntiles) read_k(buf_next, kh, ka);
-            __builtin_amdgcn_sched_barrier(0);
-            pv(va, pb);
-            if (t + 1 < ntiles) qk(ka, st);
-            __builtin_amdgcn_sched_barrier(0);
-            buf = buf_next;
         }
+        turn(t, buf, tile_base);
+        if (t + 1 < ntiles) read_k(buf_next, kh, ka);
+        __builtin_amdgcn_sched_barrier(0);
+        pv(va, pb);
+        if (t + 1 < ntiles) qk(ka, st);
+        __builtin_amdgcn_sched_barrier(0);
+        buf = buf_next;
+    };
+    read_k(0, kh, ka);
+    qk(ka, st);
+    for (int t = 0; t < ntiles; ++t) body(t);
+    if constexpr (KS == 2) {
         // Merge of the two key shares of a row block.  Both carry O~ and l relative to their own
         // reference m_ref; the share of block 1 hands its state over through the (now idle) tile
         // buffers, lane for lane, and the share of block 0 rescales both to the larger reference.
@@ -489,12 +625,13 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     }
 
     // epilogue: lane (n, g2) holds, for its row, dh = 32 db + 8 (v/4) + 4 g2 + (v%4)
+    const float v_unit = KV8 ? a.v_scale[hk] : 1.f;  // KV8: V = v_scale * code value
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32);
         if (rg_of[rb] < 0) continue;
         if (a.nsplit == 1) {
-            const float inv = 1.f / l_tot;
+            const float inv = v_unit / l_tot;
             uint16_t* op = static_cast<uint16_t*>(a.out) + (int64_t)rg_of[rb] * DH + 4 * g2;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
@@ -514,7 +651,8 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
                 for (int vq = 0; vq < 4; ++vq)
                 {   // streaming store: the partials are read once, by another kernel, and leaving them
                     // dirty in L2 only lengthens the write-back at the end of this one
-                    const f32x4 val = {o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]};
+                    f32x4 val = {o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]};
+                    if constexpr (KV8) val *= v_unit;
                     __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(po + 32 * db + 8 * vq));
                 }
             if (g2 == 0) {
@@ -526,7 +664,7 @@ __global__ __launch_bounds__(NW * 64, (RB == 1 ? 2 : 1)) void attn_mfma_kernel(A
     }
 }
 
-template <int NW, int RB, int KT, int KS = 1>
+template <int NW, int RB, int KT, int KS, bool KV8 = false>
 hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int S = a.B * a.Hkv * a.nsplit;
     const int RT = p.row_tiles;
@@ -535,7 +673,8 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int nodes_local = (RW + a.G - 1) / a.G + 1;
     // three K and three V tile buffers, the ancestor bitmasks and the parent table
     const size_t smem = (size_t)2 * 3 * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
-    auto kern = attn_mfma_kernel<NW, RB, KT, KS>;
+    auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8>;
+    const unsigned threads = (NW + (KV8 ? (NW < 4 ? NW : 4) : 0)) * 64;  // KV8: plus the loading wavefronts
     static size_t smem_allowed = 0;  // per instantiation; raising the limit again is harmless
     if (smem > smem_allowed) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -544,9 +683,9 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     }
     hipEvent_t ev0, ev1;
     if (profile_next_events(&ev0, &ev1))
-        hipExtLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(NW * 64), (uint32_t)smem, st, ev0, ev1, 0, a, RT, S);
+        hipExtLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), (uint32_t)smem, st, ev0, ev1, 0, a, RT, S);
     else
-        hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(NW * 64), smem, st, a, RT, S);
+        hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), smem, st, a, RT, S);
     return hipGetLastError();
 }
 
@@ -554,6 +693,15 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
 
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     if (p.rblocks != 1) return hipErrorInvalidValue;
+    if (a.k_scale || a.v_scale) {  // K/V held as E4M3 codes
+        if (!a.k_scale || !a.v_scale) return hipErrorInvalidValue;
+        switch (p.waves * 10 + p.kshares) {  // computing wavefronts; as many loaders again
+            case 22: return launch_cfg<2, 1, 64, 2, true>(a, p, st);
+            case 42: return launch_cfg<4, 1, 64, 2, true>(a, p, st);
+            case 41: return launch_cfg<4, 1, 64, 1, true>(a, p, st);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (p.waves * 10 + p.kshares) {
         case 41: return launch_cfg<4, 1, 64, 1>(a, p, st);
         case 61: return launch_cfg<6, 1, 64, 1>(a, p, st);

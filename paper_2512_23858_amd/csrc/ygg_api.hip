@@ -30,8 +30,9 @@ int32_t check_shape(const ygg_shape* s, bool need_kv, bool need_vocab) {
     if (!common_shape_ok(*s)) return YGG_ERR_SHAPE;
     if (s->n_nodes > kMaxNodes || s->width > kMaxWidth) return YGG_ERR_UNSUPPORTED;
     if (need_kv) {
-        if (s->kv_dtype != YGG_F32 && s->kv_dtype != YGG_BF16) return YGG_ERR_UNSUPPORTED;
+        if (s->kv_dtype != YGG_F32 && s->kv_dtype != YGG_BF16 && s->kv_dtype != YGG_FP8_E4M3) return YGG_ERR_UNSUPPORTED;
         if (s->head_dim != 64 && s->head_dim != 128) return YGG_ERR_UNSUPPORTED;
+        if (s->kv_dtype == YGG_FP8_E4M3 && s->head_dim != 128) return YGG_ERR_UNSUPPORTED;
     }
     if (need_vocab && s->vocab < 1) return YGG_ERR_SHAPE;
     return YGG_OK;
@@ -51,7 +52,8 @@ AttnPlan plan_attention(const ygg_shape& s) {
     const int64_t T = (int64_t)s.max_seq_len + s.n_nodes;
     const int64_t tiles = (T + kKeyTile - 1) / kKeyTile;
     int64_t ns;
-    p.use_mfma = s.kv_dtype == YGG_BF16 && s.head_dim == 128;
+    const bool kv8 = s.kv_dtype == YGG_FP8_E4M3;  // K/V as 8-bit codes, Q and O bf16 (head_dim 128 only)
+    p.use_mfma = (s.kv_dtype == YGG_BF16 || kv8) && s.head_dim == 128;
     if (p.use_mfma) {
         // query rows that share one K/V stream, and the workgroup shape that wastes the fewest of them
         const int R = s.n_nodes * (s.n_q_heads / s.n_kv_heads);
@@ -64,6 +66,7 @@ AttnPlan plan_attention(const ygg_shape& s) {
         auto padded = [R](int rw) { return (R + rw - 1) / rw * rw; };
         if (R <= 32) { p.waves = 2; p.kshares = 2; }
         else if (R <= 64) { p.waves = 4; p.kshares = 2; }
+        else if (kv8) { p.waves = 4; }  // 8-bit K/V: at most four computing wavefronts, the loaders take the other slots
         else if (R <= 128) { p.waves = 8; p.kshares = 2; }
         else {
             p.waves = 8;
@@ -76,7 +79,8 @@ AttnPlan plan_attention(const ygg_shape& s) {
             int w = 0, r = 0, n = 0, k = 1;
             const int got = sscanf(env, "%d,%d,%d,%d", &w, &r, &n, &k);
             if (got < 4) k = 1;
-            const bool known = r == 1 && (k == 2 ? (w == 2 || w == 4 || w == 8) : (k == 1 && (w == 4 || w == 6 || w == 8)));
+            const bool known = r == 1 && (kv8 ? (w == 4 && (k == 1 || k == 2)) || (w == 2 && k == 2)
+                                              : k == 2 ? (w == 2 || w == 4 || w == 8) : (k == 1 && (w == 4 || w == 6 || w == 8)));
             if (got >= 2 && known) { p.waves = w; p.rblocks = r; p.kshares = k; }
             if (got >= 3 && n >= 1) ns_forced = n;
         }
@@ -202,19 +206,23 @@ size_t ygg_workspace_bytes(const ygg_shape* s, int32_t op, int32_t n_layers) {
     }
 }
 
-int32_t ygg_tree_attention(const ygg_shape* s, const void* q, const void* k_cache, const void* v_cache,
-                           const int32_t* seq_lens, const void* k_tree, const void* v_tree,
-                           const int32_t* parent_idx, void* out, float* lse, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
-    if (int32_t rc = check_shape(s, true, false)) return rc;
+static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void* k_cache, const void* v_cache,
+                                   const int32_t* seq_lens, const void* k_tree, const void* v_tree,
+                                   const float* k_scale, const float* v_scale,
+                                   const int32_t* parent_idx, void* out, float* lse, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
     if (!q || !k_tree || !v_tree || !seq_lens || !parent_idx || !out) return YGG_ERR_NULL;
     if (s->max_seq_len > 0 && (!k_cache || !v_cache)) return YGG_ERR_NULL;
+    // the kernels index query rows with 31 bits and address one sequence's K/V slab with 32-bit byte offsets
+    const int64_t elem = s->kv_dtype == YGG_F32 ? 4 : s->kv_dtype == YGG_BF16 ? 2 : 1;
+    if ((int64_t)s->batch * s->n_nodes * s->n_q_heads > 0x7fffffffLL) return YGG_ERR_UNSUPPORTED;
+    if (s->kv_capacity * s->n_kv_heads * s->head_dim * elem > 0xffffffffLL) return YGG_ERR_UNSUPPORTED;
     const AttnPlan p = plan_attention(*s);
     if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes)) return rc;
 
     AttnArgs a{};
     a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
-    a.seq_lens = seq_lens; a.parent_idx = parent_idx;
+    a.seq_lens = seq_lens; a.parent_idx = parent_idx; a.k_scale = k_scale; a.v_scale = v_scale;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.part_o_bytes);
     a.out = out; a.lse = lse;
@@ -223,11 +231,33 @@ int32_t ygg_tree_attention(const ygg_shape* s, const void* q, const void* k_cach
     a.nsplit = p.nsplit; a.max_seq_len = s->max_seq_len; a.cap = s->kv_capacity; a.scale = s->softmax_scale;
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int out_dtype = s->kv_dtype == YGG_F32 ? YGG_F32 : YGG_BF16;  // element type of Q and O
     hipError_t e = p.use_mfma ? launch_attn_mfma(a, p, st) : launch_attn_vector(a, p, s->kv_dtype, st);
     if (e != hipSuccess) return YGG_ERR_LAUNCH;
     if (p.use_mfma && p.nsplit == 1) return YGG_OK;  // the kernel wrote the final rows itself
-    e = launch_attn_combine(a, p, s->kv_dtype, st);
+    e = launch_attn_combine(a, p, out_dtype, st);
     return e == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
+int32_t ygg_tree_attention(const ygg_shape* s, const void* q, const void* k_cache, const void* v_cache,
+                           const int32_t* seq_lens, const void* k_tree, const void* v_tree,
+                           const int32_t* parent_idx, void* out, float* lse, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+    if (int32_t rc = check_shape(s, true, false)) return rc;
+    if (s->kv_dtype == YGG_FP8_E4M3) return YGG_ERR_UNSUPPORTED;  // codes need their scales: ygg_tree_attention_fp8kv
+    return tree_attention_impl(s, q, k_cache, v_cache, seq_lens, k_tree, v_tree, nullptr, nullptr, parent_idx, out, lse,
+                               workspace, workspace_bytes, hip_stream);
+}
+
+int32_t ygg_tree_attention_fp8kv(const ygg_shape* s, const void* q, const void* k_cache, const void* v_cache,
+                                 const int32_t* seq_lens, const void* k_tree, const void* v_tree,
+                                 const float* k_scale, const float* v_scale, const int32_t* parent_idx, void* out,
+                                 float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (int32_t rc = check_shape(s, true, false)) return rc;
+    if (s->kv_dtype != YGG_FP8_E4M3) return YGG_ERR_UNSUPPORTED;
+    if (!k_scale || !v_scale) return YGG_ERR_NULL;
+    return tree_attention_impl(s, q, k_cache, v_cache, seq_lens, k_tree, v_tree, k_scale, v_scale, parent_idx, out, lse,
+                               workspace, workspace_bytes, hip_stream);
 }
 
 int32_t ygg_equal_growth_expand(const ygg_shape* s, int32_t d, const float* draft_logits, int32_t* parent_idx,
@@ -341,7 +371,7 @@ int32_t ygg_accept_and_compact(const ygg_shape* s, int32_t n_layers, const float
     a.old_len = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + p.part_bytes);
     a.B = s->batch; a.N = s->n_nodes; a.D = s->depth; a.V = s->vocab; a.Hkv = s->n_kv_heads; a.Dh = s->head_dim;
     a.n_layers = n_layers; a.chunk = p.chunk; a.nchunk = p.nchunk; a.max_seq_len = s->max_seq_len;
-    a.elem_bytes = s->kv_dtype == YGG_F32 ? 4 : 2; a.cap = s->kv_capacity;
+    a.elem_bytes = s->kv_dtype == YGG_F32 ? 4 : s->kv_dtype == YGG_BF16 ? 2 : 1; a.cap = s->kv_capacity;
     return launch_accept(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
 }
 

@@ -23,6 +23,8 @@ struct AttnArgs {
     const void* v_tree;
     const int32_t* seq_lens;
     const int32_t* parent_idx;
+    const float* k_scale;  // [Hkv], both set: K and V hold 8-bit E4M3 codes; both null: plain elements
+    const float* v_scale;
     float* part_o;    // [nsplit][B*N*Hq][Dh]
     float* part_ml;   // [nsplit][B*N*Hq][2]   (running max m in scaled-score units, sum l)
     void* out;

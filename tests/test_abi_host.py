@@ -81,6 +81,34 @@ def test_attention_rejects_bad_arguments_on_the_host():
     assert _call_attention(_shape(), good, ws=0x1000, ws_bytes=need - 1) == ERR_WORKSPACE  # too small
 
 
+def test_8bit_kv_attention_rejects_bad_arguments_on_the_host():
+    lib = ygg.load_library()
+
+    def call(shape, ptrs, ws=0x1000, ws_bytes=1 << 30):
+        cs = shape.c()
+        return lib.ygg_tree_attention_fp8kv(ctypes.byref(cs), *[ctypes.c_void_p(p) for p in ptrs],
+                                            ctypes.c_void_p(ws), ctypes.c_size_t(ws_bytes), None)
+    good = [FAKE] * 10 + [0]   # q kc vc lens kt vt k_scale v_scale parent out, lse = NULL
+    s8 = _shape(kv_dtype=2)
+    for i in (0, 3, 4, 5, 6, 7, 8, 9):
+        bad = list(good)
+        bad[i] = 0
+        assert call(s8, bad) == ERR_NULL
+    assert call(_shape(kv_dtype=1), good) == ERR_UNSUPPORTED                 # codes need kv_dtype FP8_E4M3
+    assert call(_shape(kv_dtype=2, head_dim=64), good) == ERR_UNSUPPORTED
+    assert call(s8, good, ws_bytes=16) == ERR_WORKSPACE
+    assert _call_attention(s8, [FAKE] * 8 + [0], ws=0x1000, ws_bytes=1 << 30) == ERR_UNSUPPORTED   # no scales there
+    # a K/V slab of one sequence is addressed with 32-bit byte offsets
+    huge = _shape(kv_dtype=1, n_kv_heads=8, max_seq_len=3_000_000, kv_capacity=3_000_010)
+    assert _call_attention(huge, [FAKE] * 8 + [0], ws=0x1000, ws_bytes=1 << 40) == ERR_UNSUPPORTED
+    # 8-bit K/V: at most four computing wavefronts (the loaders take the other slots), in pairs for small trees
+    for n_nodes, depth, width, exp in ((13, 3, 4, dict(waves=4, key_shares=2, row_tiles=1)),     # R = 52
+                                       (5, 1, 4, dict(waves=2, key_shares=2, row_tiles=1)),      # R = 20
+                                       (129, 8, 16, dict(waves=4, key_shares=1, row_tiles=5))):  # R = 516
+        got = ygg.attention_plan(_shape(kv_dtype=2, n_nodes=n_nodes, depth=depth, width=width))
+        assert got["matrix_cores"] and all(got[k] == v for k, v in exp.items()), got
+
+
 def test_expand_rejects_bad_arguments_on_the_host():
     lib = ygg.load_library()
 

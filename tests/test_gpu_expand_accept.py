@@ -77,18 +77,22 @@ def test_expand_is_deterministic():
     assert all(np.array_equal(x.view(np.int32), y.view(np.int32)) for x, y in zip(a, b))
 
 
-def _accept_both(cfg, parent, token, layers, lens, logits=None, tstar=None, depth=None):
+def _accept_both(cfg, parent, token, layers, lens, logits=None, tstar=None, depth=None, codes=False):
     B, N = parent.shape
     D = cfg.depth if depth is None else depth
     max_len = int(lens.max())
     cap = max_len + D + 1
     mk = lambda s, n: wl.normal(cfg.seed, s, (layers, B, n, cfg.n_kv_heads, cfg.head_dim), cfg.dtype)
+    if codes:   # K/V held as 8-bit codes: compaction moves bytes, any byte pattern will do
+        mk = lambda s, n: wl.rng(cfg.seed, s).integers(0, 256, size=(layers, B, n, cfg.n_kv_heads, cfg.head_dim), dtype=np.uint8)
     kt, vt, kc, vc = mk(5, N), mk(6, N), mk(3, cap), mk(4, cap)
     lens = lens.astype(np.int32).copy()
     g = [to_dev(a.copy()) for a in (kt, vt, kc, vc, lens)]
     ref = oracle.accept_compact(D + 1, parent, token, kt, vt, kc, vc, lens, target_logits=logits, target_tokens=tstar)
     shape = shape_of(cfg, max_seq_len=max_len, kv_capacity=cap, n_nodes=N)
     shape.depth = D
+    if codes:
+        shape.kv_dtype = ygg.FP8_E4M3
     alen = torch.full((B,), -5, dtype=torch.int32, device=DEV)
     apath = torch.full((B, D + 1), -5, dtype=torch.int32, device=DEV)
     bonus = torch.full((B,), -5, dtype=torch.int32, device=DEV)
@@ -115,6 +119,14 @@ def test_accept_shapes(B, D, W, V, dtype, layers):
     logits = wl.acceptance_inputs(wl.scaled(cfg, agree=(0.8,)), parent, token)
     lens = wl.rng(cfg.seed, 50).integers(0, 40, size=B)
     ref = _accept_both(cfg, parent, token, layers, lens, logits=logits)
+    assert ref["accept_len"].max() > 1
+
+
+def test_accept_compacts_8bit_caches():
+    cfg = _cfg(3, 5, 4, 2000, Dh=128)
+    parent = wl.trees(cfg); token = wl.tokens(cfg, parent)
+    logits = wl.acceptance_inputs(wl.scaled(cfg, agree=(0.8,)), parent, token)
+    ref = _accept_both(cfg, parent, token, 2, np.array([7, 0, 33]), logits=logits, codes=True)
     assert ref["accept_len"].max() > 1
 
 
