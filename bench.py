@@ -28,12 +28,14 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 FP32_VALU_PEAK_TFLOPS = 157.3
 
 
-def attention_work(cfg, lens):
-    """Algorithmic bytes and flops of one tree-attention layer."""
+def attention_work(cfg, lens, kv_bytes=None):
+    """Algorithmic bytes and flops of one tree-attention layer (kv_bytes: bytes of a stored K/V element
+    when it differs from the element size of Q and O)."""
     e = 4 if cfg.dtype == "f32" else 2
+    ekv = e if kv_bytes is None else kv_bytes
     N, Hq, Hkv, Dh, B = cfg.n_nodes, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.batch
     sumL = int(np.sum(lens))
-    nbytes = 2 * sumL * Hkv * Dh * e + 2 * B * N * Hkv * Dh * e + 2 * B * N * Hq * Dh * e
+    nbytes = 2 * sumL * Hkv * Dh * ekv + 2 * B * N * Hkv * Dh * ekv + 2 * B * N * Hq * Dh * e
     flops = 4 * N * Hq * Dh * (sumL + B * N)
     return nbytes, flops
 
@@ -71,6 +73,8 @@ def main():
     ap.add_argument("--growth", choices=["frontier", "attach"], default="frontier",
                     help="draft-step rule: children of the previous depth only (default, the metric's definition) "
                          "or free attachment anywhere in the partial tree")
+    ap.add_argument("--kv", choices=["native", "fp8"], default="native",
+                    help="fp8: K/V stored as 8-bit E4M3 codes with per-kv-head scales (bf16 configurations, head_dim 128)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every call from the host instead of replaying one captured HIP graph per step")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -106,6 +110,12 @@ def main():
     if args.batch:
         cfg = wl.scaled(cfg, batch=args.batch)
         variant += f" with batch {args.batch}"
+    kv8 = args.kv == "fp8"
+    if kv8:
+        if cfg.dtype != "bf16" or cfg.head_dim != 128:
+            print("bench.py: --kv fp8 needs a bf16 configuration with head_dim 128", file=sys.stderr)
+            sys.exit(2)
+        variant += " with 8-bit K/V"
     n_layers = args.layers or cfg.n_layers
     B, N, D, W, V = cfg.batch, cfg.n_nodes, cfg.depth, cfg.width, cfg.vocab
     Hkv, Dh, cap = cfg.n_kv_heads, cfg.head_dim, cfg.kv_capacity
@@ -121,17 +131,22 @@ def main():
     parent_h = wl.trees(cfg)
     token_h = wl.tokens(cfg, parent_h)
     q = torch.empty((n_layers, B, N, cfg.n_q_heads, Dh), dtype=tdt, device=dev)
-    k_cache = torch.empty((n_layers, B, cap, Hkv, Dh), dtype=tdt, device=dev)
+    kvdt = torch.uint8 if kv8 else tdt
+    k_cache = torch.empty((n_layers, B, cap, Hkv, Dh), dtype=kvdt, device=dev)
     v_cache = torch.empty_like(k_cache)
-    k_tree = torch.empty((n_layers, B, N, Hkv, Dh), dtype=tdt, device=dev)
+    k_tree = torch.empty((n_layers, B, N, Hkv, Dh), dtype=kvdt, device=dev)
     v_tree = torch.empty_like(k_tree)
+    k_scale = torch.ones((n_layers, Hkv), dtype=torch.float32, device=dev)
+    v_scale = torch.ones_like(k_scale)
     layer0 = None
     for layer in range(n_layers):
-        h = wl.attention_inputs(cfg, layer=layer, lens=lens_h)
+        h = (wl.attention_inputs_fp8kv if kv8 else wl.attention_inputs)(cfg, layer=layer, lens=lens_h)
         if layer == 0:
             layer0 = h
         q[layer], k_cache[layer], v_cache[layer] = up(h["q"]), up(h["k_cache"]), up(h["v_cache"])
         k_tree[layer], v_tree[layer] = up(h["k_tree"]), up(h["v_tree"])
+        if kv8:
+            k_scale[layer], v_scale[layer] = up(h["k_scale"]), up(h["v_scale"])
     out = torch.empty_like(q)
     draft_h = [wl.expansion_inputs(cfg, d) for d in range(1, D + 1)]
     draft = [up(x) for x in draft_h]
@@ -148,7 +163,7 @@ def main():
     bonus = torch.zeros((B,), dtype=torch.int32, device=dev)
 
     shape = ygg.Shape(batch=B, n_q_heads=cfg.n_q_heads, n_kv_heads=Hkv, head_dim=Dh, depth=D, width=W, n_nodes=N,
-                      vocab=V, kv_dtype=0 if cfg.dtype == "f32" else 1, softmax_scale=cfg.softmax_scale,
+                      vocab=V, kv_dtype=2 if kv8 else 0 if cfg.dtype == "f32" else 1, softmax_scale=cfg.softmax_scale,
                       kv_capacity=cap, max_seq_len=cfg.max_prefix)
     ws = [torch.empty(max(ygg.workspace_bytes(shape, op, n_layers), 256), dtype=torch.uint8, device=dev)
           for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT)]
@@ -160,8 +175,12 @@ def main():
 
     def attention_pass():
         for layer in range(n_layers):
-            ygg.tree_attention(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer], v_tree[layer],
-                               parent, out[layer], None, ws[0])
+            if kv8:
+                ygg.tree_attention_fp8kv(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer],
+                                         v_tree[layer], k_scale[layer], v_scale[layer], parent, out[layer], None, ws[0])
+            else:
+                ygg.tree_attention(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer], v_tree[layer],
+                                   parent, out[layer], None, ws[0])
 
     def step():
         lens.copy_(lens0)   # acceptance advances seq_lens; every step starts from the same state
@@ -284,7 +303,7 @@ def main():
     for _ in range(args.steps):
         eager_body()
     kern_us, kern_n = ygg.profile_end()
-    nbytes, flops = attention_work(cfg, lens_h)
+    nbytes, flops = attention_work(cfg, lens_h, kv_bytes=1 if kv8 else None)
     t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
     if cfg.dtype == "f32":
         bound, peak, unit, ach = "alu", FP32_VALU_PEAK_TFLOPS, "TFLOP/s", flops / (kern_us * 1e-6) / 1e12
@@ -313,15 +332,25 @@ def main():
             # the oracle's full routine parallelises over rows; sampled rows go through the row routine
             for r in sel:
                 b_, i_, h_ = r // (N * cfg.n_q_heads), (r // cfg.n_q_heads) % N, r % cfg.n_q_heads
-                oracle.attention_row(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
-                                     layer0["v_tree"], parent_h, cfg.softmax_scale, int(b_), int(i_), int(h_))
+                if kv8:
+                    oracle.attention_row_fp8kv(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                               layer0["v_tree"], layer0["k_scale"], layer0["v_scale"], parent_h,
+                                               cfg.softmax_scale, int(b_), int(i_), int(h_))
+                else:
+                    oracle.attention_row(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                         layer0["v_tree"], parent_h, cfg.softmax_scale, int(b_), int(i_), int(h_))
         run_rows(rs)
         per_row_serial = (time.perf_counter() - t) / probe
         est_full = per_row_serial * rows_all / threads
         if est_full <= 20.0:
             t = time.perf_counter()
-            oracle.tree_attention(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
-                                  layer0["v_tree"], parent_h, cfg.softmax_scale)
+            if kv8:
+                oracle.tree_attention_fp8kv(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                            layer0["v_tree"], layer0["k_scale"], layer0["v_scale"], parent_h,
+                                            cfg.softmax_scale)
+            else:
+                oracle.tree_attention(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                      layer0["v_tree"], parent_h, cfg.softmax_scale)
             t_attn_layer = time.perf_counter() - t
             attn_note = "attention: all rows of layer 0 (OpenMP over rows)"
         else:

@@ -95,16 +95,15 @@ __device__ __forceinline__ u32x4 global_load16(uint64_t gaddr) {
     return *reinterpret_cast<const __attribute__((address_space(1))) u32x4*>(gaddr);
 }
 
-// Sixteen E4M3 codes (memory order) -> sixteen bf16; exact, the format has 3 mantissa bits.
+// Sixteen E4M3 codes (memory order) -> sixteen bf16; exact, the format has 3 mantissa bits.  One
+// conversion instruction per pair of codes (scale operand 1.0).
 __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& raw, uint4& first8, uint4& last8) {
     const uint32_t w[4] = {raw[0], raw[1], raw[2], raw[3]};
     uint32_t o[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], false);  // bytes 0, 1
-        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[i], true);   // bytes 2, 3
-        o[2 * i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2));
-        o[2 * i + 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2));
+        o[2 * i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[i], 1.0f, false));     // bytes 0, 1
+        o[2 * i + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[i], 1.0f, true));  // bytes 2, 3
     }
     first8 = make_uint4(o[0], o[1], o[2], o[3]);
     last8 = make_uint4(o[4], o[5], o[6], o[7]);
@@ -114,6 +113,14 @@ template <int V>
 struct IntC {
     static constexpr int value = V;
 };
+// f(IntC<I>{}) for I = FROM .. TO-1, unrolled at compile time
+template <int FROM, int TO, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (FROM < TO) {
+        f(IntC<FROM>{});
+        static_for<FROM + 1, TO>(f);
+    }
+}
 
 // NW wavefronts, RB 32-row blocks per wavefront, KT keys per tile, KS key shares: with KS = 2 the
 // wavefronts pair up on the same rows and each takes one of the two 32-key blocks of every tile (a
@@ -123,14 +130,15 @@ struct IntC {
 // KV8: K and V are stored as 8-bit E4M3 codes with one scale per kv head.  The codes are widened
 // to bf16 on their way into LDS (exactly), so tiles, operand reads and matrix work are those of
 // the bf16 kernel; the scales fold into the softmax scale and into the final normalisation.  The
-// direct-to-LDS path cannot convert, so the workgroup gets NLD extra wavefronts that do nothing but
-// load codes into registers (four tiles ahead), widen them and store the rows into the tile
-// buffers; the NW computing wavefronts never touch global K/V.  Both kinds meet at the same one
-// barrier per tile.
+// direct-to-LDS path cannot convert, so the workgroup gets four extra wavefronts that do nothing but
+// load codes into registers (four tiles ahead; eight measured no faster), widen them and store the
+// rows into the tile buffers; the NW computing wavefronts never touch global K/V.  Both kinds meet
+// at the same one barrier per tile.
 template <int NW, int RB, int KT, int KS, bool KV8>
-__global__ __launch_bounds__((NW + (KV8 ? (NW < 4 ? NW : 4) : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
+__global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
     static_assert(KS == 1 || (KS == 2 && NW % 2 == 0 && KT == 64), "key shares: one block of the tile each");
-    constexpr int NLD = KV8 ? (NW < 4 ? NW : 4) : 0;             // loading wavefronts (KV8 only)
+    constexpr int NLD = KV8 ? 4 : 0;                             // loading wavefronts (KV8 only)
+    constexpr int NSET = 4;                                      // register sets (tiles in flight) per loader
     constexpr int THREADS = (NW + NLD) * 64;
     static_assert(!KV8 || NW <= 4, "loading wavefronts share the SIMDs with at most one computing wavefront each");
     constexpr int NRW = NW / KS;                                 // wavefronts along the rows
@@ -302,10 +310,31 @@ __global__ __launch_bounds__((NW + (KV8 ? (NW < 4 ? NW : 4) : 0)) * 64, (RB == 1
         u32x4 d[LPT];
     };
     const int lw = wave - NW;
+    // per-lane constants of this loader's LPT loads: byte offset inside a tile of cache rows, and the
+    // two LDS byte offsets (relative to buffer 0) its sixteen widened values go to
+    uint32_t ld_off[LPT], st_off0[LPT], st_off1[LPT];
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) {
+        const bool is_v = it * NLD >= 8;  // known once the loop is unrolled
+        const int row = 8 * ((lw + it * NLD) & 7) + (lane >> 3);
+        const int c2 = 2 * (lane & 7);    // this lane's two 16-byte slots: c2, c2 + 1
+        const int x = is_v ? ((row & 3) << 2) : (row & 15);
+        ld_off[it] = (uint32_t)row * tok_bytes + 16 * (lane & 7);
+        st_off0[it] = (is_v ? NBUF * TILEB : 0) + row * ROWB + 16 * (c2 ^ x);
+        st_off1[it] = (is_v ? NBUF * TILEB : 0) + row * ROWB + 16 * ((c2 + 1) ^ x);
+    }
+    const int cache_end = min(L, k1);
     auto stage_issue = [&](Stage& sg, int tile_base) {
+        if (tile_base + KT <= cache_end) {  // a whole tile of cache rows: uniform base + constant per-lane offsets
+            const uint64_t kb = (uint64_t)kc + (uint64_t)((uint32_t)tile_base * tok_bytes);
+            const uint64_t vb = (uint64_t)vc + (uint64_t)((uint32_t)tile_base * tok_bytes);
+#pragma unroll
+            for (int it = 0; it < LPT; ++it) sg.d[it] = global_load16((it * NLD >= 8 ? vb : kb) + ld_off[it]);
+            return;
+        }
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
-            const bool is_v = it * NLD >= 8;  // known once the loop is unrolled
+            const bool is_v = it * NLD >= 8;
             const int row = 8 * ((lw + it * NLD) & 7) + (lane >> 3);
             const int j = min(tile_base + row, k1 - 1);
             const bool in_cache = j < L;
@@ -316,17 +345,13 @@ __global__ __launch_bounds__((NW + (KV8 ? (NW < 4 ? NW : 4) : 0)) * 64, (RB == 1
     };
     // widens the staged codes and stores them where the direct-to-LDS path would have put the bf16 row
     auto stage_write = [&](const Stage& sg, int buf) {
+        unsigned char* base = smem + buf * TILEB;
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
-            const bool is_v = it * NLD >= 8;  // known once the loop is unrolled
-            const int row = 8 * ((lw + it * NLD) & 7) + (lane >> 3);
-            const int c2 = 2 * (lane & 7);  // this lane's two 16-byte slots: c2, c2 + 1
             uint4 w0, w1;
             e4m3x16_to_bf16(sg.d[it], w0, w1);
-            unsigned char* r = smem + (is_v ? NBUF * TILEB : 0) + buf * TILEB + row * ROWB;
-            const int x = is_v ? ((row & 3) << 2) : (row & 15);
-            *reinterpret_cast<uint4*>(r + 16 * (c2 ^ x)) = w0;
-            *reinterpret_cast<uint4*>(r + 16 * ((c2 + 1) ^ x)) = w1;
+            *reinterpret_cast<uint4*>(base + st_off0[it]) = w0;
+            *reinterpret_cast<uint4*>(base + st_off1[it]) = w1;
         }
     };
 
@@ -476,41 +501,35 @@ __global__ __launch_bounds__((NW + (KV8 ? (NW < 4 ? NW : 4) : 0)) * 64, (RB == 1
         }
     };
 
-    // KV8, loading wavefronts.  Tile tau travels in register set tau & 3; iteration t (after the
+    // KV8, loading wavefronts.  Tile tau travels in register set tau % NSET; iteration t (after the
     // barrier that retires tile t) stores tile t+3 into tile t's buffer and reuses the set for the
-    // loads of tile t+7.  Every staged load is issued whether or not its tile exists: the number
-    // of loads in flight at each point is then the same on every path, and the compiler's wait for
-    // one register set leaves the three younger sets in flight.  The barriers match those of the
-    // computing wavefronts one for one.
+    // loads of tile t+3+NSET.  Every staged load is issued whether or not its tile exists: the
+    // number of loads in flight at each point is then the same on every path, and the compiler's
+    // wait for one register set leaves the NSET-1 younger sets in flight.  The barriers match those
+    // of the computing wavefronts one for one.
     if constexpr (KV8) {
         if (is_loader) {
-            Stage stage[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) stage_issue(stage[i], k0 + i * KT);
+            Stage stage[NSET];
+            static_for<0, NSET>([&](auto i) { stage_issue(stage[i.value], k0 + i.value * KT); });
             build_masks();
-#pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                stage_write(stage[i], i);
-                stage_issue(stage[i], k0 + (4 + i) * KT);
-            }
+            static_for<0, 3>([&](auto i) {
+                stage_write(stage[i.value], i.value);
+                stage_issue(stage[i.value], k0 + (NSET + i.value) * KT);
+            });
             lds_barrier();  // tiles 0..2 are in LDS for everybody; anc_s published
             int lbuf = 0;
             auto lstep = [&](int t, Stage& sg) {
                 lds_barrier();
                 if (t + 3 < ntiles) stage_write(sg, lbuf);
-                stage_issue(sg, k0 + (t + 7) * KT);
+                stage_issue(sg, k0 + (t + 3 + NSET) * KT);
                 lbuf = lbuf + 1 == NBUF ? 0 : lbuf + 1;
             };
             int t = 0;
-            for (; t + 3 < ntiles; t += 4) {
-                lstep(t, stage[3]);
-                lstep(t + 1, stage[0]);
-                lstep(t + 2, stage[1]);
-                lstep(t + 3, stage[2]);
-            }
-            if (t < ntiles) lstep(t, stage[3]);
-            if (t + 1 < ntiles) lstep(t + 1, stage[0]);
-            if (t + 2 < ntiles) lstep(t + 2, stage[1]);
+            for (; t + NSET - 1 < ntiles; t += NSET)
+                static_for<0, NSET>([&](auto i) { lstep(t + i.value, stage[(i.value + 3) % NSET]); });
+            static_for<0, NSET - 1>([&](auto i) {
+                if (t + i.value < ntiles) lstep(t + i.value, stage[(i.value + 3) % NSET]);
+            });
             if constexpr (KS == 2) {  // the merge of the key shares has two more workgroup barriers
                 __syncthreads();
                 __syncthreads();
@@ -674,7 +693,7 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     // three K and three V tile buffers, the ancestor bitmasks and the parent table
     const size_t smem = (size_t)2 * 3 * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
     auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8>;
-    const unsigned threads = (NW + (KV8 ? (NW < 4 ? NW : 4) : 0)) * 64;  // KV8: plus the loading wavefronts
+    const unsigned threads = (NW + (KV8 ? 4 : 0)) * 64;  // KV8: plus the four loading wavefronts
     static size_t smem_allowed = 0;  // per instantiation; raising the limit again is harmless
     if (smem > smem_allowed) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -695,7 +714,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st
     if (p.rblocks != 1) return hipErrorInvalidValue;
     if (a.k_scale || a.v_scale) {  // K/V held as E4M3 codes
         if (!a.k_scale || !a.v_scale) return hipErrorInvalidValue;
-        switch (p.waves * 10 + p.kshares) {  // computing wavefronts; as many loaders again
+        switch (p.waves * 10 + p.kshares) {  // computing wavefronts; four loaders on top
             case 22: return launch_cfg<2, 1, 64, 2, true>(a, p, st);
             case 42: return launch_cfg<4, 1, 64, 2, true>(a, p, st);
             case 41: return launch_cfg<4, 1, 64, 1, true>(a, p, st);
