@@ -53,6 +53,45 @@ def test_attention_full_size(config, layer, sample_rows):
     _attention_check(wl.CONFIGS[config], layer, sample_rows)
 
 
+@pytest.mark.parametrize("config,layer,sample_rows", [(2, 0, None), (3, 5, 300), (5, 0, 300)])
+def test_attention_full_size_8bit_kv(config, layer, sample_rows):
+    """The bf16 configurations at full size with K/V stored as E4M3 codes (same draws, quantised per kv head)."""
+    cfg = wl.CONFIGS[config]
+    lens = wl.seq_lens(cfg)
+    parent = wl.trees(cfg)
+    host = wl.attention_inputs_fp8kv(cfg, layer=layer, lens=lens)
+    shape = shape_of(cfg)
+    shape.kv_dtype = ygg.FP8_E4M3
+    d = {k: to_dev(np.ascontiguousarray(v)) for k, v in host.items()}
+    out_t = torch.full_like(d["q"], float("nan"))
+    lse_t = torch.full(d["q"].shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    ygg.tree_attention_fp8kv(shape, d["q"], d["k_cache"], d["v_cache"], d["seq_lens"], d["k_tree"], d["v_tree"],
+                             d["k_scale"], d["v_scale"], to_dev(parent), out_t, lse_t, workspace(shape, ygg.OP_ATTENTION))
+    torch.cuda.synchronize()
+    out, lse = out_t.double().cpu().numpy(), lse_t.double().cpu().numpy()
+    B, N, Hq = cfg.batch, cfg.n_nodes, cfg.n_q_heads
+    args = (host["q"], host["k_cache"], host["v_cache"], lens, host["k_tree"], host["v_tree"], host["k_scale"],
+            host["v_scale"], parent, cfg.softmax_scale)
+    if sample_rows is None:
+        ref_out, ref_lse = oracle.tree_attention_fp8kv(*args)
+        got_out, got_lse = out, lse
+    else:
+        g = wl.rng(cfg.seed, 71, sub=layer)
+        picks = {(int(g.integers(B)), int(g.integers(N)), int(g.integers(Hq))) for _ in range(sample_rows)}
+        picks = sorted(picks | {(0, 0, 0), (B - 1, N - 1, Hq - 1)})
+        ref_out = np.empty((len(picks), cfg.head_dim)); ref_lse = np.empty(len(picks))
+        for k, (b, i, h) in enumerate(picks):
+            ref_out[k], ref_lse[k] = oracle.attention_row_fp8kv(*args, b, i, h)
+        idx = tuple(np.array(picks).T)
+        got_out, got_lse = out[idx], lse[idx]
+    err = np.abs(got_out - ref_out)
+    assert err.max() <= 2e-2 and err.mean() <= 1e-2, (err.max(), err.mean())
+    rms = np.sqrt((ref_out ** 2).mean())
+    assert np.sqrt((err ** 2).mean()) <= 0.02 * rms, (np.sqrt((err ** 2).mean()), rms)
+    assert np.abs(got_lse - ref_lse).max() <= 1e-3
+    assert np.isfinite(out).all() and np.isfinite(lse).all()
+
+
 @pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
 def test_expansion_full_size(config):
     cfg = wl.CONFIGS[config]

@@ -18,7 +18,7 @@ def _bits(t):
 
 
 @pytest.mark.parametrize("growth", ["frontier", "attach"])
-@pytest.mark.parametrize("which", ["tiny_fp32", "bf16_matrix_cores"])
+@pytest.mark.parametrize("which", ["tiny_fp32", "bf16_matrix_cores", "8bit_kv"])
 def test_captured_step_replays_like_the_eager_step(which, growth):
     if which == "tiny_fp32":
         cfg, layers = wl.CONFIGS[1], 2
@@ -27,10 +27,16 @@ def test_captured_step_replays_like_the_eager_step(which, growth):
                                 seed=31), 3
     B, N, D, W = cfg.batch, cfg.n_nodes, cfg.depth, cfg.width
     shape = shape_of(cfg)
+    codes = which == "8bit_kv"
+    if codes:
+        shape.kv_dtype = ygg.FP8_E4M3
     cap = cfg.kv_capacity
     lens_h = wl.seq_lens(cfg)
     draft = [to_dev(wl.expansion_inputs(cfg, d)) for d in range(1, D + 1)]
-    per_layer = [wl.attention_inputs(cfg, layer=l, lens=lens_h) for l in range(layers)]
+    per_layer = [(wl.attention_inputs_fp8kv if codes else wl.attention_inputs)(cfg, layer=l, lens=lens_h)
+                 for l in range(layers)]
+    if codes:
+        k_scale, v_scale = (to_dev(np.stack([h[k] for h in per_layer])) for k in ("k_scale", "v_scale"))
     stack = lambda k: to_dev(np.stack([h[k] for h in per_layer]))
     q, k_tree, v_tree = stack("q"), stack("k_tree"), stack("v_tree")
     k_cache0, v_cache0 = stack("k_cache"), stack("v_cache")
@@ -56,8 +62,12 @@ def test_captured_step_replays_like_the_eager_step(which, growth):
             else:
                 ygg.equal_growth_attach(shape, d, draft[d - 1], parent, token, cum, pool, ws[ygg.OP_ATTACH])
         for l in range(layers):
-            ygg.tree_attention(shape, q[l], k_cache[l], v_cache[l], lens, k_tree[l], v_tree[l], parent, out[l], None,
-                               ws[ygg.OP_ATTENTION])
+            if codes:
+                ygg.tree_attention_fp8kv(shape, q[l], k_cache[l], v_cache[l], lens, k_tree[l], v_tree[l], k_scale[l],
+                                         v_scale[l], parent, out[l], None, ws[ygg.OP_ATTENTION])
+            else:
+                ygg.tree_attention(shape, q[l], k_cache[l], v_cache[l], lens, k_tree[l], v_tree[l], parent, out[l], None,
+                                   ws[ygg.OP_ATTENTION])
         ygg.accept_and_compact(shape, layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens, alen, apath, bonus,
                                target_logits=target, workspace=ws[ygg.OP_ACCEPT])
 

@@ -17,7 +17,7 @@ def _bits(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.cpu().numpy()
 
 
-@pytest.mark.parametrize("which", ["fp32_vector_path", "bf16_matrix_cores_ragged_batch"])
+@pytest.mark.parametrize("which", ["fp32_vector_path", "bf16_matrix_cores_ragged_batch", "8bit_kv_ragged_batch"])
 def test_three_steps_chained_on_the_device(which):
     steps = 3
     if which == "fp32_vector_path":
@@ -32,8 +32,16 @@ def test_three_steps_chained_on_the_device(which):
     cap = max_len + D + 1
     cfg = wl.scaled(base, prefix_len=max_len, prefix_range=())
     shape = shape_of(cfg, max_seq_len=max_len, kv_capacity=cap)
+    codes = which.startswith("8bit")   # K/V as E4M3 codes: what compaction appends is what the next attention decodes
 
     mk = lambda stream, n: wl.normal(cfg.seed, stream, (layers, B, n, cfg.n_kv_heads, cfg.head_dim), cfg.dtype)
+    if codes:
+        shape.kv_dtype = ygg.FP8_E4M3
+        mk = lambda stream, n: wl.f64_to_fp8_e4m3_bits(
+            wl.normal(cfg.seed, stream, (layers, B, n, cfg.n_kv_heads, cfg.head_dim), "f32").astype(np.float64) * 64.0)
+        k_scale = np.array([1 / 64.0, 1 / 50.0], np.float32)
+        v_scale = np.array([1 / 70.0, 1 / 64.0], np.float32)
+        g_ks, g_vs = to_dev(k_scale), to_dev(v_scale)
     kc, vc = mk(3, cap), mk(4, cap)
     lens = lens0.copy()
     g_kc, g_vc, g_lens = to_dev(kc.copy()), to_dev(vc.copy()), to_dev(lens.copy())
@@ -56,10 +64,18 @@ def test_three_steps_chained_on_the_device(which):
         g_q, g_kt, g_vt = to_dev(q), to_dev(kt), to_dev(vt)
         g_out = torch.empty_like(g_q)
         for l in range(layers):
-            ygg.tree_attention(shape, g_q[l], g_kc[l], g_vc[l], g_lens, g_kt[l], g_vt[l], g_parent, g_out[l], None,
-                               ws[ygg.OP_ATTENTION])
-        ref_out = np.stack([oracle.tree_attention(q[l], kc[l], vc[l], lens, kt[l], vt[l], parent, cfg.softmax_scale)[0]
-                            for l in range(layers)])
+            if codes:
+                ygg.tree_attention_fp8kv(shape, g_q[l], g_kc[l], g_vc[l], g_lens, g_kt[l], g_vt[l], g_ks, g_vs, g_parent,
+                                         g_out[l], None, ws[ygg.OP_ATTENTION])
+            else:
+                ygg.tree_attention(shape, g_q[l], g_kc[l], g_vc[l], g_lens, g_kt[l], g_vt[l], g_parent, g_out[l], None,
+                                   ws[ygg.OP_ATTENTION])
+        if codes:
+            ref_out = np.stack([oracle.tree_attention_fp8kv(q[l], kc[l], vc[l], lens, kt[l], vt[l], k_scale, v_scale, parent,
+                                                            cfg.softmax_scale)[0] for l in range(layers)])
+        else:
+            ref_out = np.stack([oracle.tree_attention(q[l], kc[l], vc[l], lens, kt[l], vt[l], parent, cfg.softmax_scale)[0]
+                                for l in range(layers)])
         # acceptance: the target agrees with the draft now and then; lengths and caches advance on the device
         target = wl.acceptance_inputs(wl.scaled(cfg, seed=seed), parent, token)
         ref = oracle.accept_compact(D + 1, parent, token, kt, vt, kc, vc, lens, target_logits=target)

@@ -252,9 +252,16 @@ def attention_inputs_fp8kv(cfg: Config, layer: int = 0, lens: np.ndarray | None 
         tree = normal(s, st, (B, N, Hkv, Dh), "f32")
         amax = np.maximum(np.abs(cache).max(axis=(0, 1, 3)), np.abs(tree).max(axis=(0, 1, 3)))
         scale = (amax / np.float32(448.0)).astype(np.float32)
-        bc = scale.astype(np.float64)[None, None, :, None]
-        out[name + "_cache"] = f64_to_fp8_e4m3_bits(cache / bc)
-        out[name + "_tree"] = f64_to_fp8_e4m3_bits(tree / bc)
+        bc = scale.astype(np.float64)[None, :, None]
+
+        def quantise(x):   # in slices of 1024 tokens: the float64 temporaries stay small
+            codes = np.empty(x.shape, np.uint8)
+            flat_x, flat_c = x.reshape(-1, Hkv, Dh), codes.reshape(-1, Hkv, Dh)
+            for lo in range(0, flat_x.shape[0], 1024):
+                flat_c[lo:lo + 1024] = f64_to_fp8_e4m3_bits(flat_x[lo:lo + 1024] / bc)
+            return codes
+        out[name + "_cache"] = quantise(cache)
+        out[name + "_tree"] = quantise(tree)
         out[name + "_scale"] = scale
     return out
 
