@@ -18,6 +18,9 @@
 //                      which is exactly the accumulator layout of S^T packed to bf16
 // The tree's own keys are the tail of the key range; their ancestor mask comes from per-node
 // bitmasks built in LDS from parent_idx.
+//
+// The same kernel also serves K/V stored as 8-bit E4M3 codes (template flag KV8): extra loading
+// wavefronts widen the codes to bf16 while filling the LDS tiles, everything else is shared.
 #include "ygg_internal.h"
 
 #include <hip/hip_ext.h>
