@@ -233,6 +233,7 @@ int32_t ygg_prune_for_verification(const ygg_shape *shape, int32_t w_verify,
  *   parent_idx, token_ids [B,N] int32
  *   k_tree, v_tree   [n_layers,B,N,Hkv,Dh]    kv_dtype (may be NULL when n_layers == 0)
  *   k_cache, v_cache [n_layers,B,cap,Hkv,Dh]  kv_dtype, updated in place
+ *                    (with YGG_FP8_E4M3 the four K/V arrays hold one-byte codes; rows are copied as bytes)
  *   seq_lens [B] int32 in/out; accept_len [B], accept_path [B,D+1], bonus_token [B] int32 out
  */
 int32_t ygg_accept_and_compact(const ygg_shape *shape, int32_t n_layers,
