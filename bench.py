@@ -43,7 +43,7 @@ def attention_work(cfg, lens, kv_bytes=None):
 # HBM bytes per launch of the attention main kernel (fetched + written), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs
 # scaled by a streaming kernel of known size; a benchmark run cannot collect counters itself, so the figures measured with
 # the commands recorded in profiles/attn_mfma_hbm_traffic.md are carried here, per workload configuration.
-MEASURED_TRAFFIC_BYTES = {2: 26_450_227, 3: 37_865_267, 4: 177_698_509, 5: 329_497_497}
+MEASURED_TRAFFIC_BYTES = {2: 26_075_033, 3: 37_865_267, 4: 177_698_509, 5: 329_497_497}
 
 
 def cpu_model():
