@@ -132,3 +132,25 @@ def test_attention_is_deterministic(dtype):
     a_out, a_lse = run_attention(shape, host, parent, poison=0xA5)
     b_out, b_lse = run_attention(shape, host, parent, poison=0x00)
     assert np.array_equal(a_out, b_out) and np.array_equal(a_lse, b_lse)
+
+
+@pytest.mark.parametrize("dtype,Dh", [("bf16", 128), ("f32", 64)])
+def test_empty_cache_with_null_cache_pointers(dtype, Dh):
+    """First step after an empty prompt: max_seq_len = 0, so the caches may be NULL; every node sees only its
+    ancestors and itself."""
+    import torch
+    import paper_2512_23858_amd as ygg
+    from gpu_util import DEV, to_dev, to_f64, workspace
+    cfg, host, parent = _inputs(_cfg(2, 8, 4, 4, 5, dtype=dtype, Dh=Dh), [0, 0], 0)
+    ref_out, ref_lse = oracle.tree_attention(host["q"], host["k_cache"], host["v_cache"], host["seq_lens"],
+                                             host["k_tree"], host["v_tree"], parent, cfg.softmax_scale)
+    shape = shape_of(cfg, max_seq_len=0)
+    d = {k: to_dev(np.ascontiguousarray(v)) for k, v in host.items()}
+    out = torch.full_like(d["q"], float("nan"))
+    lse = torch.full(d["q"].shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    ygg.tree_attention(shape, d["q"], None, None, d["seq_lens"], d["k_tree"], d["v_tree"], to_dev(parent), out, lse,
+                       workspace(shape, ygg.OP_ATTENTION))
+    torch.cuda.synchronize()
+    tol = 1e-5 if dtype == "f32" else 2e-2
+    assert np.abs(to_f64(out) - ref_out).max() <= tol
+    assert np.abs(to_f64(lse) - ref_lse).max() <= (1e-5 if dtype == "f32" else 1e-3)

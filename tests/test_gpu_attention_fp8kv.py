@@ -176,3 +176,16 @@ def test_is_deterministic():
     a = _run(_shape(cfg, 640), host, parent)
     b = _run(_shape(cfg, 640), host, parent)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_empty_cache_with_null_cache_pointers():
+    cfg, host, parent = _inputs(_cfg(2, 8, 4, 4, 5), [0, 0], 0)
+    ref_out, ref_lse = _oracle(cfg, host, parent)
+    shape = _shape(cfg, 0)
+    d = {k: to_dev(np.ascontiguousarray(v)) for k, v in host.items()}
+    out = torch.full_like(d["q"], float("nan"))
+    lse = torch.full(d["q"].shape[:3], float("nan"), dtype=torch.float32, device=DEV)
+    ygg.tree_attention_fp8kv(shape, d["q"], None, None, d["seq_lens"], d["k_tree"], d["v_tree"], d["k_scale"], d["v_scale"],
+                             to_dev(parent), out, lse, workspace(shape, ygg.OP_ATTENTION))
+    torch.cuda.synchronize()
+    assert np.abs(to_f64(out) - ref_out).max() <= 2e-2 and np.abs(to_f64(lse) - ref_lse).max() <= 1e-3
