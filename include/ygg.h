@@ -22,10 +22,10 @@
  *     default stream) and never synchronise, so a sequence of calls can be captured in a HIP
  *     graph.  All shapes are static: nothing on the host depends on device data.  This is the
  *     static-runtime property the paper asks of the drafting algorithm (Sec. 3, Sec. 4.2).
- *     The first call that uses a given kernel variant raises that kernel's dynamic shared-memory
- *     limit (a host-side function attribute): run every shape once eagerly before capturing it.
- *     That bookkeeping is the library's only state; it is not synchronised, so the first calls of a
- *     process should come from one thread.
+ *     The first launching call on a device (or ygg_init) raises the dynamic shared-memory limits
+ *     of the library's kernels, once, under a lock; call ygg_init before capturing if the first
+ *     call of a process would otherwise be made under stream capture.  That per-device flag is
+ *     the library's only state.
  *   - The return code reports host-checkable errors only (null pointers, inconsistent shape,
  *     unsupported type, workspace too small, launch failure).  Data-dependent contract
  *     violations (parent_idx not topological, seq_lens[b] > max_seq_len, NaN logits) are
@@ -76,7 +76,7 @@ typedef struct {
     int32_t n_nodes;       /* N (1..1024); must equal 1 + D*W for ygg_equal_growth_expand */
     int32_t vocab;         /* V (only used by expand / accept) */
     int32_t kv_dtype;      /* ygg_dtype of Q, K, V and O (see YGG_FP8_E4M3 for the mixed case) */
-    float softmax_scale;   /* multiplies q.k; typically 1/sqrt(Dh) */
+    float softmax_scale;   /* multiplies q.k; typically 1/sqrt(Dh); must be finite and > 0 where K/V are used */
     int64_t kv_capacity;   /* token slots per sequence in the cache, >= max_seq_len + D + 1 */
     int32_t max_seq_len;   /* host-known upper bound of seq_lens[b] (sizes the launch grids) */
 } ygg_shape;
@@ -86,6 +86,13 @@ size_t ygg_workspace_bytes(const ygg_shape *shape, int32_t op /* ygg_op */, int3
 
 /* Static, human-readable name of a status code. */
 const char *ygg_status_string(int32_t status);
+
+/*
+ * Optional: prepares the current device (raises the kernels' shared-memory limits).  Every launching
+ * call does the same on first use; calling it up front keeps that out of a stream capture.  Thread safe.
+ * Returns YGG_ERR_LAUNCH when there is no usable device.
+ */
+int32_t ygg_init(void);
 
 /*
  * Tree-masked verify attention for one layer (paper Sec. 2 "Source of Improvements": the
@@ -270,6 +277,14 @@ int32_t ygg_debug_validate(const ygg_shape *shape, const int32_t *parent_idx, co
  * plan[4] = key splits (the last three are 0 / meaningless for the vector kernel except plan[4]).
  */
 int32_t ygg_debug_attention_plan(const ygg_shape *shape, int32_t *plan /* [5], host */);
+
+/*
+ * Tuning hook: forces the workgroup shape (wavefronts, 32-row blocks per wavefront, key shares) and/or the number
+ * of key splits of every later ygg_tree_attention call of this process; a field left 0 keeps the library's own
+ * choice, an unknown shape is ignored, and (0, 0, 0, 0) removes the override.  The workspace must be sized
+ * (ygg_workspace_bytes) while the same override is in force.  Process-wide; meant for sweeps, not for production.
+ */
+int32_t ygg_debug_set_attention_plan(int32_t waves, int32_t rblocks, int32_t nsplit, int32_t kshares);
 
 /*
  * Measurement hook for benchmarks (not part of the verification path; not thread-safe).

@@ -12,11 +12,13 @@ from .binding import (  # noqa: F401
     debug_validate,
     equal_growth_attach,
     equal_growth_expand,
+    init,
     lib_path,
     load_library,
     profile_begin,
     profile_end,
     prune_for_verification,
+    set_attention_plan,
     status_string,
     tree_attention,
     tree_attention_fp8kv,

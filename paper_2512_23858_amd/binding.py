@@ -86,6 +86,10 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_debug_validate.argtypes = [shp] + [vp] * 4 + [i32, vp, vp]
         lib.ygg_accept_and_compact.restype = i32
         lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
+        lib.ygg_init.restype = i32
+        lib.ygg_init.argtypes = []
+        lib.ygg_debug_set_attention_plan.restype = i32
+        lib.ygg_debug_set_attention_plan.argtypes = [i32, i32, i32, i32]
         lib.ygg_debug_attention_plan.restype = i32
         lib.ygg_debug_attention_plan.argtypes = [shp, ctypes.POINTER(i32)]
         lib.ygg_profile_begin.restype = i32
@@ -244,6 +248,16 @@ def attention_plan(shape: Shape) -> dict:
     out = (ctypes.c_int32 * 5)()
     _check(load_library().ygg_debug_attention_plan(ctypes.byref(cs), out), "ygg_debug_attention_plan")
     return dict(matrix_cores=bool(out[0]), waves=out[1], key_shares=out[2], row_tiles=out[3], key_splits=out[4])
+
+
+def init():
+    """ygg_init: prepares the current device up front (otherwise done by the first launching call)."""
+    _check(load_library().ygg_init(), "ygg_init")
+
+
+def set_attention_plan(waves: int = 0, rblocks: int = 0, nsplit: int = 0, kshares: int = 0):
+    """ygg_debug_set_attention_plan: tuning override of the attention launch plan (all zero: none)."""
+    _check(load_library().ygg_debug_set_attention_plan(waves, rblocks, nsplit, kshares), "ygg_debug_set_attention_plan")
 
 
 def profile_begin(max_launches: int):

@@ -700,6 +700,16 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     }
 }
 
+// Largest dynamic shared memory any shape asks for: six 16 KiB tiles, ancestor masks of up to 257 nodes x 32 words, and
+// the parent table of 1024 nodes.  Every variant's limit is raised to it once per device.
+constexpr size_t kMaxSmem = (size_t)2 * 3 * 64 * ROWB + (size_t)257 * 32 * 4 + 1024 * 4;
+
+template <int NW, int RB, int KT, int KS, bool KV8, bool NT>
+hipError_t raise_variant() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<NW, RB, KT, KS, KV8, NT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxSmem);
+}
+
 template <int NW, int RB, int KT, int KS, bool KV8, bool NT>
 hipError_t launch_variant(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int S = a.B * a.Hkv * a.nsplit;
@@ -711,12 +721,7 @@ hipError_t launch_variant(const AttnArgs& a, const AttnPlan& p, hipStream_t st) 
     const size_t smem = (size_t)2 * 3 * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
     auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8, NT>;
     const unsigned threads = (NW + (KV8 ? 4 : 0)) * 64;  // KV8: plus the four loading wavefronts
-    static size_t smem_allowed = 0;  // per instantiation; raising the limit again is harmless
-    if (smem > smem_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        smem_allowed = smem;
-    }
+    if (smem > kMaxSmem) return hipErrorInvalidValue;  // cannot happen for N <= 1024: checked again for the sake of the launch
     hipEvent_t ev0, ev1;
     if (profile_next_events(&ev0, &ev1))
         hipExtLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), (uint32_t)smem, st, ev0, ev1, 0, a, RT, S);
@@ -736,6 +741,20 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
 }
 
 }  // namespace
+
+hipError_t raise_limits_attn_mfma() {
+    hipError_t e = hipSuccess;
+    auto both = [&](auto nw, auto ks) {
+        if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, false>();
+        if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, true>();
+    };
+    both(IntC<4>{}, IntC<1>{}); both(IntC<6>{}, IntC<1>{}); both(IntC<8>{}, IntC<1>{});
+    both(IntC<2>{}, IntC<2>{}); both(IntC<4>{}, IntC<2>{}); both(IntC<8>{}, IntC<2>{});
+    if (e == hipSuccess) e = raise_variant<2, 1, 64, 2, true, false>();
+    if (e == hipSuccess) e = raise_variant<4, 1, 64, 2, true, false>();
+    if (e == hipSuccess) e = raise_variant<4, 1, 64, 1, true, false>();
+    return e;
+}
 
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     if (p.rblocks != 1) return hipErrorInvalidValue;

@@ -114,6 +114,9 @@ __device__ __forceinline__ void wave_top_w(Get get, int W, int wave, int lane, T
         base += (int)__popcll(m);
     }
     fits = base <= kPoolCap && base >= want;
+    // the ranking below reads pool entries written by other lanes of this wavefront
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     if (fits) {
         // rank the pooled candidates against each other; the best `want` go out in order
         const int C = base;
@@ -518,6 +521,15 @@ ExpandPlan plan_expand(const ygg_shape& s, int32_t d) {
     return p;
 }
 
+// Static plus dynamic LDS of these two exceeds the 64 KiB default.
+hipError_t raise_limits_expand() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(expand_merge_kernel<16>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_scratch_bytes(16));
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(attach_pool_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)(4096 * sizeof(Entry)));
+}
+
 hipError_t launch_expand(const ExpandArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(expand_scan_kernel, dim3((unsigned)(a.B * a.F), (unsigned)a.nchunk), dim3(kScanThreads), 0, st, a);
     hipError_t e = hipGetLastError();
@@ -529,13 +541,6 @@ hipError_t launch_expand(const ExpandArgs& a, hipStream_t st) {
     } else if (K <= 1024) {
         hipLaunchKernelGGL(expand_merge_kernel<4>, grid, block, merge_scratch_bytes(4), st, a);
     } else {
-        static bool raised = false;  // static + dynamic LDS of this instantiation exceeds the 64 KiB default
-        if (!raised) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(expand_merge_kernel<16>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_scratch_bytes(16));
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
         hipLaunchKernelGGL(expand_merge_kernel<16>, grid, block, merge_scratch_bytes(16), st, a);
     }
     return hipGetLastError();

@@ -2,8 +2,9 @@
 // is done here other than enqueuing kernels on the caller's stream; nothing synchronises.
 #include "ygg_internal.h"
 
-#include <cstdio>
-#include <cstdlib>
+#include <atomic>
+#include <cmath>
+#include <mutex>
 #include <vector>
 
 namespace ygg {
@@ -14,6 +15,16 @@ struct ProfileState {
     size_t used = 0;
     std::vector<hipEvent_t> start, stop;
 } g_profile;
+
+// Launch-plan override for tuning runs (ygg_debug_set_attention_plan): waves << 24 | rblocks << 16 | kshares << 8 in the
+// upper word, the forced split count in the lower; 0 = no override.
+std::atomic<uint64_t> g_plan_override{0};
+
+// One-time set-up per device: every kernel variant that needs more dynamic shared memory than the default gets its limit
+// raised, so that no later call (possibly under stream capture) has to.
+constexpr int kMaxDevices = 64;
+std::atomic<bool> g_device_ready[kMaxDevices];
+std::mutex g_init_mutex;
 
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
@@ -33,6 +44,8 @@ int32_t check_shape(const ygg_shape* s, bool need_kv, bool need_vocab) {
         if (s->kv_dtype != YGG_F32 && s->kv_dtype != YGG_BF16 && s->kv_dtype != YGG_FP8_E4M3) return YGG_ERR_UNSUPPORTED;
         if (s->head_dim != 64 && s->head_dim != 128) return YGG_ERR_UNSUPPORTED;
         if (s->kv_dtype == YGG_FP8_E4M3 && s->head_dim != 128) return YGG_ERR_UNSUPPORTED;
+        // the matrix-core kernel takes row maxima before scaling, which needs a positive finite scale
+        if (!(s->softmax_scale > 0.f) || !std::isfinite(s->softmax_scale)) return YGG_ERR_SHAPE;
     }
     if (need_vocab && s->vocab < 1) return YGG_ERR_SHAPE;
     return YGG_OK;
@@ -75,14 +88,12 @@ AttnPlan plan_attention(const ygg_shape& s) {
             if (padded(192) * 100 <= best * 80) { p.waves = 6; p.kshares = 1; }
         }
         int64_t ns_forced = 0;
-        if (const char* env = getenv("YGG_ATTN_PLAN")) {  // tuning knob: "waves,rblocks[,nsplit[,kshares]]"
-            int w = 0, r = 0, n = 0, k = 1;
-            const int got = sscanf(env, "%d,%d,%d,%d", &w, &r, &n, &k);
-            if (got < 4) k = 1;
+        if (const uint64_t ov = g_plan_override.load(std::memory_order_relaxed)) {
+            const int w = (int)(ov >> 56), r = (int)(ov >> 48) & 0xff, k = (int)(ov >> 40) & 0xff;
             const bool known = r == 1 && (kv8 ? (w == 4 && (k == 1 || k == 2)) || (w == 2 && k == 2)
                                               : k == 2 ? (w == 2 || w == 4 || w == 8) : (k == 1 && (w == 4 || w == 6 || w == 8)));
-            if (got >= 2 && known) { p.waves = w; p.rblocks = r; p.kshares = k; }
-            if (got >= 3 && n >= 1) ns_forced = n;
+            if (known) { p.waves = w; p.rblocks = r; p.kshares = k; }
+            ns_forced = (int64_t)(ov & 0xffffffffu);
         }
         const int rw = p.waves / p.kshares * p.rblocks * 32;
         p.row_tiles = (R + rw - 1) / rw;
@@ -117,11 +128,32 @@ bool profile_next_events(hipEvent_t* start, hipEvent_t* stop) {
     return true;
 }
 
+// Raises the shared-memory limits of the current device's kernels once; later calls cost one atomic load.
+int32_t ensure_device_ready() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return YGG_ERR_LAUNCH;
+    if (g_device_ready[dev].load(std::memory_order_acquire)) return YGG_OK;
+    std::lock_guard<std::mutex> lock(g_init_mutex);
+    if (g_device_ready[dev].load(std::memory_order_relaxed)) return YGG_OK;
+    if (raise_limits_attn_mfma() != hipSuccess || raise_limits_expand() != hipSuccess) return YGG_ERR_LAUNCH;
+    g_device_ready[dev].store(true, std::memory_order_release);
+    return YGG_OK;
+}
+
 }  // namespace ygg
 
 using namespace ygg;
 
 extern "C" {
+
+int32_t ygg_init(void) { return ensure_device_ready(); }
+
+int32_t ygg_debug_set_attention_plan(int32_t waves, int32_t rblocks, int32_t nsplit, int32_t kshares) {
+    if (waves < 0 || waves > 255 || rblocks < 0 || rblocks > 255 || kshares < 0 || kshares > 255 || nsplit < 0) return YGG_ERR_SHAPE;
+    g_plan_override.store(((uint64_t)waves << 56) | ((uint64_t)rblocks << 48) | ((uint64_t)kshares << 40) | (uint32_t)nsplit,
+                          std::memory_order_relaxed);
+    return YGG_OK;
+}
 
 int32_t ygg_debug_attention_plan(const ygg_shape* s, int32_t* plan) {
     if (int32_t rc = check_shape(s, true, false)) return rc;
@@ -219,6 +251,7 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     if (s->kv_capacity * s->n_kv_heads * s->head_dim * elem > 0xffffffffLL) return YGG_ERR_UNSUPPORTED;
     const AttnPlan p = plan_attention(*s);
     if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes)) return rc;
+    if (int32_t rc = ensure_device_ready()) return rc;
 
     AttnArgs a{};
     a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
@@ -273,6 +306,7 @@ int32_t ygg_equal_growth_expand(const ygg_shape* s, int32_t d, const float* draf
     if ((int64_t)p.F * s->vocab >= 0x7fffffffLL) return YGG_ERR_UNSUPPORTED;  // flat candidate index is 32 bits
     if ((int64_t)s->batch * p.F > 0x7fffffffLL || p.nchunk > 65535) return YGG_ERR_UNSUPPORTED;
     if (int32_t rc = check_workspace(workspace, workspace_bytes, p.stat_bytes + p.cand_bytes)) return rc;
+    if (int32_t rc = ensure_device_ready()) return rc;
 
     ExpandArgs a{};
     a.logits = draft_logits; a.parent_idx = parent_idx; a.token_ids = token_ids; a.cum_logprob = cum_logprob;
@@ -305,6 +339,7 @@ int32_t ygg_equal_growth_attach(const ygg_shape* s, int32_t t, const float* draf
     if ((reinterpret_cast<uintptr_t>(pool) & 15u) != 0 || pool_bytes < attach_pool_bytes(*s)) return YGG_ERR_WORKSPACE;
     const size_t offer_bytes = attach_offer_bytes(*s);
     if (int32_t rc = check_workspace(workspace, workspace_bytes, p.stat_bytes + p.cand_bytes + offer_bytes)) return rc;
+    if (int32_t rc = ensure_device_ready()) return rc;
 
     ExpandArgs a{};
     a.logits = draft_logits; a.parent_idx = parent_idx; a.token_ids = token_ids; a.cum_logprob = cum_logprob;

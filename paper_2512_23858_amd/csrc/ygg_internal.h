@@ -50,6 +50,11 @@ hipError_t launch_attn_vector(const AttnArgs& a, const AttnPlan& p, int dtype, h
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st);
 hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
 
+// One-time raising of the dynamic shared-memory limits of every kernel variant of a translation unit (current device).
+hipError_t raise_limits_attn_mfma();
+hipError_t raise_limits_expand();
+int32_t ensure_device_ready();
+
 // Measurement hook: when profiling is on, returns a fresh (start, stop) event pair for the next
 // attention main-kernel launch and true; otherwise false.
 bool profile_next_events(hipEvent_t* start, hipEvent_t* stop);

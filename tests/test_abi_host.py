@@ -75,6 +75,8 @@ def test_attention_rejects_bad_arguments_on_the_host():
     assert _call_attention(_shape(head_dim=96), good) == ERR_UNSUPPORTED
     assert _call_attention(_shape(kv_dtype=5), good) == ERR_UNSUPPORTED
     assert _call_attention(_shape(n_nodes=5000), good) == ERR_UNSUPPORTED
+    for bad_scale in (0.0, -0.125, float("inf"), float("nan")):     # row maxima are taken before scaling
+        assert _call_attention(_shape(softmax_scale=bad_scale), good) == ERR_SHAPE
     need = ygg.workspace_bytes(_shape(), ygg.OP_ATTENTION)
     assert _call_attention(_shape(), good, ws=0, ws_bytes=need) == ERR_WORKSPACE           # missing
     assert _call_attention(_shape(), good, ws=0x1010, ws_bytes=need) == ERR_WORKSPACE      # misaligned
@@ -206,10 +208,9 @@ def test_shape_struct_layout_matches_header():
     assert _CShape.kv_capacity.offset == 40 and _CShape.max_seq_len.offset == 48
 
 
-def test_attention_plans_of_the_five_configurations(monkeypatch):
+def test_attention_plans_of_the_five_configurations():
     """The launch shapes the measurements were taken with (a change here is a performance change)."""
     import ygg_workloads as wl
-    monkeypatch.delenv("YGG_ATTN_PLAN", raising=False)
     want = {1: dict(matrix_cores=False),
             2: dict(matrix_cores=True, waves=4, key_shares=2, row_tiles=1, key_splits=6),
             3: dict(matrix_cores=True, waves=8, key_shares=2, row_tiles=5, key_splits=6),
@@ -229,3 +230,26 @@ def test_attention_plans_of_the_five_configurations(monkeypatch):
     p = ygg.attention_plan(s2)
     rows = s2.batch * s2.n_nodes * s2.n_q_heads
     assert ygg.workspace_bytes(s2, ygg.OP_ATTENTION) >= p["key_splits"] * rows * 130 * 4
+
+
+def test_plan_override_is_explicit_and_removable():
+    """The tuning override is a call, not an environment variable, and leaves no trace once removed."""
+    import os
+    s = _shape(max_seq_len=4096, kv_capacity=4200)
+    base = ygg.attention_plan(s)
+    os.environ["YGG_ATTN_PLAN"] = "8,1,3,2"
+    try:
+        assert ygg.attention_plan(s) == base            # the environment is not consulted
+    finally:
+        del os.environ["YGG_ATTN_PLAN"]
+    ygg.set_attention_plan(nsplit=3)
+    try:
+        forced = ygg.attention_plan(s)
+        assert forced["key_splits"] == 3 and forced["waves"] == base["waves"]
+        ygg.set_attention_plan(waves=2, rblocks=1, kshares=2)
+        assert ygg.attention_plan(s)["waves"] == 2 and ygg.attention_plan(s)["key_shares"] == 2
+        ygg.set_attention_plan(waves=5, rblocks=1, kshares=1)   # unknown shape: ignored
+        assert ygg.attention_plan(s)["waves"] == base["waves"]
+    finally:
+        ygg.set_attention_plan()
+    assert ygg.attention_plan(s) == base

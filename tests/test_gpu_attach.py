@@ -72,7 +72,9 @@ def attach_both(cfg, logits_fn=None, check_margin=True, sigma=1.0):
 
 
 @pytest.mark.parametrize("B,D,W,V", [(1, 3, 4, 1000), (2, 4, 8, 4097), (3, 2, 1, 50), (2, 5, 16, 32000), (1, 3, 7, 13),
-                                     (1, 6, 8, 32000), (1, 4, 32, 20000), (1, 2, 56, 9000), (4, 3, 5, 4096), (1, 1, 6, 700), (1, 8, 8, 32000), (1, 16, 8, 32000)])
+                                     (1, 6, 8, 32000), (1, 4, 32, 20000), (1, 2, 56, 9000), (4, 3, 5, 4096), (1, 1, 6, 700), (1, 8, 8, 32000), (1, 16, 8, 32000),
+                                     # > 1024 list entries per row, and a pool sort over 4096 slots (the widest the call accepts)
+                                     (1, 2, 40, 128256), (1, 2, 60, 128256)])
 def test_attach_shapes(B, D, W, V):
     attach_both(_cfg(B, D, W, V))
 

@@ -1,7 +1,7 @@
 """GPU parity at the full sizes of the five workload configurations, in the launch configuration the
-benchmark times (same shapes, same plan).  Attention is compared on every output row where the oracle
-finishes in seconds (configurations 1-3) and on sampled rows otherwise; expansion indices, accepted
-paths and compacted cache bytes are compared exactly everywhere."""
+benchmark times (same shapes, same plan).  Attention is compared on every output row and every
+log-sum-exp of a whole layer (the oracle runs its rows in parallel: about 20 s for the widest tree);
+expansion indices, accepted paths and compacted cache bytes are compared exactly everywhere."""
 import numpy as np
 import pytest
 import torch
@@ -14,48 +14,38 @@ from gpu_util import DEV, run_attention, shape_of, to_dev, workspace
 pytestmark = pytest.mark.gpu
 
 
-def _attention_check(cfg, layer, sample_rows):
-    lens = wl.seq_lens(cfg)
-    parent = wl.trees(cfg)
-    host = wl.attention_inputs(cfg, layer=layer, lens=lens)
-    out, lse = run_attention(shape_of(cfg), host, parent)
-    B, N, Hq = cfg.batch, cfg.n_nodes, cfg.n_q_heads
-    if sample_rows is None:
-        ref_out, ref_lse = oracle.tree_attention(host["q"], host["k_cache"], host["v_cache"], lens, host["k_tree"],
-                                                 host["v_tree"], parent, cfg.softmax_scale)
-        got_out, got_lse = out, lse
-    else:
-        g = wl.rng(cfg.seed, 70, sub=layer)
-        picks = {(int(g.integers(B)), int(g.integers(N)), int(g.integers(Hq))) for _ in range(sample_rows)}
-        picks |= {(0, 0, 0), (B - 1, N - 1, Hq - 1)}
-        picks = sorted(picks)
-        ref_out = np.empty((len(picks), cfg.head_dim)); ref_lse = np.empty(len(picks))
-        for k, (b, i, h) in enumerate(picks):
-            ref_out[k], ref_lse[k], _ = oracle.attention_row(host["q"], host["k_cache"], host["v_cache"], lens,
-                                                             host["k_tree"], host["v_tree"], parent,
-                                                             cfg.softmax_scale, b, i, h)
-        idx = tuple(np.array(picks).T)
-        got_out, got_lse = out[idx], lse[idx]
-    err = np.abs(got_out - ref_out)
+def _gates(cfg, out, lse, ref_out, ref_lse):
+    err = np.abs(out - ref_out)
     if cfg.dtype == "f32":
-        assert err.max() <= 1e-5 and np.abs(got_lse - ref_lse).max() <= 1e-5
+        assert err.max() <= 1e-5 and np.abs(lse - ref_lse).max() <= 1e-5
     else:
         assert err.max() <= 2e-2 and err.mean() <= 1e-2, (err.max(), err.mean())
         rms = np.sqrt((ref_out ** 2).mean())
         assert np.sqrt((err ** 2).mean()) <= 0.02 * rms, (np.sqrt((err ** 2).mean()), rms)
-        assert np.abs(got_lse - ref_lse).max() <= 1e-3
+        assert np.abs(lse - ref_lse).max() <= 1e-3
+        # no row tile, key split or kv head may hide behind the averages: the same relative bound per node
+        row_rms = np.sqrt((err ** 2).mean(axis=(2, 3)))                     # [B, N]
+        assert (row_rms <= 0.05 * rms).all(), float(row_rms.max() / rms)
     assert np.isfinite(out).all() and np.isfinite(lse).all()
 
 
-@pytest.mark.parametrize("config,layer,sample_rows", [(1, 0, None), (2, 0, None), (2, 31, None), (3, 0, None),
-                                                      (3, 17, 300), (4, 0, 200), (4, 31, 60), (5, 0, 400)])
-def test_attention_full_size(config, layer, sample_rows):
-    _attention_check(wl.CONFIGS[config], layer, sample_rows)
+@pytest.mark.parametrize("config,layer", [(1, 0), (2, 0), (2, 31), (3, 0), (3, 17), (4, 0), (4, 31), (5, 0)])
+def test_attention_full_size(config, layer):
+    """Every output row and every log-sum-exp of the layer against the oracle."""
+    cfg = wl.CONFIGS[config]
+    lens = wl.seq_lens(cfg)
+    parent = wl.trees(cfg)
+    host = wl.attention_inputs(cfg, layer=layer, lens=lens)
+    out, lse = run_attention(shape_of(cfg), host, parent)
+    ref_out, ref_lse = oracle.tree_attention(host["q"], host["k_cache"], host["v_cache"], lens, host["k_tree"],
+                                             host["v_tree"], parent, cfg.softmax_scale)
+    _gates(cfg, out, lse, ref_out, ref_lse)
 
 
-@pytest.mark.parametrize("config,layer,sample_rows", [(2, 0, None), (3, 5, 300), (5, 0, 300)])
-def test_attention_full_size_8bit_kv(config, layer, sample_rows):
-    """The bf16 configurations at full size with K/V stored as E4M3 codes (same draws, quantised per kv head)."""
+@pytest.mark.parametrize("config,layer", [(2, 0), (3, 5), (5, 0)])
+def test_attention_full_size_8bit_kv(config, layer):
+    """The bf16 configurations at full size with K/V stored as E4M3 codes (same draws, quantised per kv head);
+    every row of the layer."""
     cfg = wl.CONFIGS[config]
     lens = wl.seq_lens(cfg)
     parent = wl.trees(cfg)
@@ -69,27 +59,10 @@ def test_attention_full_size_8bit_kv(config, layer, sample_rows):
                              d["k_scale"], d["v_scale"], to_dev(parent), out_t, lse_t, workspace(shape, ygg.OP_ATTENTION))
     torch.cuda.synchronize()
     out, lse = out_t.double().cpu().numpy(), lse_t.double().cpu().numpy()
-    B, N, Hq = cfg.batch, cfg.n_nodes, cfg.n_q_heads
-    args = (host["q"], host["k_cache"], host["v_cache"], lens, host["k_tree"], host["v_tree"], host["k_scale"],
-            host["v_scale"], parent, cfg.softmax_scale)
-    if sample_rows is None:
-        ref_out, ref_lse = oracle.tree_attention_fp8kv(*args)
-        got_out, got_lse = out, lse
-    else:
-        g = wl.rng(cfg.seed, 71, sub=layer)
-        picks = {(int(g.integers(B)), int(g.integers(N)), int(g.integers(Hq))) for _ in range(sample_rows)}
-        picks = sorted(picks | {(0, 0, 0), (B - 1, N - 1, Hq - 1)})
-        ref_out = np.empty((len(picks), cfg.head_dim)); ref_lse = np.empty(len(picks))
-        for k, (b, i, h) in enumerate(picks):
-            ref_out[k], ref_lse[k] = oracle.attention_row_fp8kv(*args, b, i, h)
-        idx = tuple(np.array(picks).T)
-        got_out, got_lse = out[idx], lse[idx]
-    err = np.abs(got_out - ref_out)
-    assert err.max() <= 2e-2 and err.mean() <= 1e-2, (err.max(), err.mean())
-    rms = np.sqrt((ref_out ** 2).mean())
-    assert np.sqrt((err ** 2).mean()) <= 0.02 * rms, (np.sqrt((err ** 2).mean()), rms)
-    assert np.abs(got_lse - ref_lse).max() <= 1e-3
-    assert np.isfinite(out).all() and np.isfinite(lse).all()
+    ref_out, ref_lse = oracle.tree_attention_fp8kv(host["q"], host["k_cache"], host["v_cache"], lens, host["k_tree"],
+                                                   host["v_tree"], host["k_scale"], host["v_scale"], parent,
+                                                   cfg.softmax_scale)
+    _gates(cfg, out, lse, ref_out, ref_lse)
 
 
 @pytest.mark.parametrize("config", [1, 2, 3, 4, 5])

@@ -40,7 +40,8 @@ def _expand_both(cfg, logits_fn=None, check_margin=True):
 
 
 @pytest.mark.parametrize("B,D,W,V", [(1, 3, 4, 1000), (2, 4, 8, 4097), (3, 2, 1, 50), (1, 2, 64, 9000),
-                                     (2, 5, 16, 32000), (1, 3, 7, 13), (4, 3, 5, 4096), (1, 8, 8, 32000), (1, 16, 8, 32000)])
+                                     (2, 5, 16, 32000), (1, 3, 7, 13), (4, 3, 5, 4096), (1, 8, 8, 32000), (1, 16, 8, 32000),
+                                     (1, 2, 40, 128256), (1, 2, 64, 128256)])   # the last two: > 1024 chunk lists per sequence
 def test_expand_shapes(B, D, W, V):
     _expand_both(_cfg(B, D, W, V))
 
