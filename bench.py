@@ -77,6 +77,7 @@ def main():
                     help="fp8: K/V stored as 8-bit E4M3 codes with per-kv-head scales (bf16 configurations, head_dim 128)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch every call from the host instead of replaying one captured HIP graph per step")
+    ap.add_argument("--plan", default="", help="tuning: force the attention launch plan, waves,rblocks,nsplit,kshares (0 = library's choice)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB streaming kernel, dst = 2*src (reference point for HBM traffic counters)")
     args = ap.parse_args()
@@ -93,6 +94,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     ygg.load_library()  # fails loudly if libygg.so is missing
+    if args.plan:
+        ygg.set_attention_plan(*(int(x) for x in args.plan.split(",")))
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.config]
     variant = ""
@@ -165,12 +168,11 @@ def main():
     shape = ygg.Shape(batch=B, n_q_heads=cfg.n_q_heads, n_kv_heads=Hkv, head_dim=Dh, depth=D, width=W, n_nodes=N,
                       vocab=V, kv_dtype=2 if kv8 else 0 if cfg.dtype == "f32" else 1, softmax_scale=cfg.softmax_scale,
                       kv_capacity=cap, max_seq_len=cfg.max_prefix)
-    ws = [torch.empty(max(ygg.workspace_bytes(shape, op, n_layers), 256), dtype=torch.uint8, device=dev)
-          for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT)]
+    ws = [ygg.new_workspace(shape, op, n_layers, device=dev) for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT)]
 
     ws_attach = pool = None
     if args.growth == "attach":
-        ws_attach = torch.empty(ygg.workspace_bytes(shape, ygg.OP_ATTACH), dtype=torch.uint8, device=dev)
+        ws_attach = ygg.new_workspace(shape, ygg.OP_ATTACH, device=dev)
         pool = torch.empty(ygg.attach_pool_bytes(shape), dtype=torch.uint8, device=dev)
 
     def attention_pass():

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     init,
     lib_path,
     load_library,
+    new_workspace,
     profile_begin,
     profile_end,
     prune_for_verification,
@@ -23,6 +24,8 @@ from .binding import (  # noqa: F401
     tree_attention,
     tree_attention_fp8kv,
     workspace_bytes,
+    workspace_init,
+    WORKSPACE_HEADER_BYTES,
     OP_ATTENTION,
     OP_EXPAND,
     OP_ACCEPT,

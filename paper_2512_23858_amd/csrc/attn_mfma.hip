@@ -21,7 +21,7 @@
 //
 // The same kernel also serves K/V stored as 8-bit E4M3 codes (template flag KV8): extra loading
 // wavefronts widen the codes to bf16 while filling the LDS tiles, everything else is shared.
-#include "ygg_internal.h"
+#include "attn_common.h"
 
 #include <hip/hip_ext.h>
 
@@ -31,76 +31,7 @@
 namespace ygg {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) short i16x4;
-typedef __attribute__((ext_vector_type(8))) short i16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-constexpr int DH = 128;
-constexpr int ROWB = 256;  // bytes of one K or V row (head_dim 128, bf16) = 16 slots of 16 bytes
-// LDS tiles are filled by direct-to-LDS loads (64 lanes x 16 bytes land contiguously), so rows are
-// unpadded and bank conflicts are avoided by permuting the 16-byte slots inside each row instead:
-//   K tile: slot' = slot ^ (row & 15)         16 consecutive rows read the same column conflict-free
-//   V tile: slot' = slot ^ ((row & 3) << 2)   a transpose read of 32 lanes touches 4 rows x 2 pairs of
-//                                             32 bytes: pair' = pair ^ 2*(row & 3) gives 8 distinct pairs
-// The permutation is applied on the global side (which 16 bytes a lane fetches), never in LDS.
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kRescaleGap = 8.f;  // log2 units by which a row maximum may outgrow its softmax reference
-
-__device__ __forceinline__ i16x4 lds_read_tr16(const unsigned char* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p));
-}
-
-// Direct-to-LDS load of 16 bytes per lane: lane l's data lands at LDS byte address lds_base + 16*l
-// (lds_base is wave-uniform and goes through M0).  Written as inline assembly so that the compiler
-// does not treat every later LDS read as dependent on it (it would wait for the whole prefetch
-// before each operand read); completion is awaited explicitly with dma_wait_keep() before the barrier
-// that publishes the tile.  The compiler keeps nothing live in M0 on this target.
-// NT adds the streaming hint: used when the stream is read by one workgroup only (one row tile), so that
-// nothing would ever hit the lines in L2 again.
-template <bool NT>
-__device__ __forceinline__ void dma_load16(const void* base /* wave-uniform */, uint32_t byte_off, uint32_t lds_base) {
-    if constexpr (NT)
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_base), "v"(byte_off), "s"(base) : "memory");
-    else
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(byte_off), "s"(base) : "memory");
-}
-// Same with a per-lane 64-bit address.
-template <bool NT>
-__device__ __forceinline__ void dma_load16_flat(const void* gptr, uint32_t lds_base) {
-    if constexpr (NT)
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_base), "v"(gptr) : "memory");
-    else
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
-}
-// Waits until at most KEEP of this wavefront's vector-memory operations are still outstanding (they
-// complete in issue order, so the KEEP youngest may still be in flight).
-template <int KEEP>
-__device__ __forceinline__ void dma_wait_keep() {
-    static_assert(KEEP >= 0 && KEEP <= 63, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KEEP) : "memory");
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    // round-to-nearest-even on both halves
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7fffu + ((a >> 16) & 1u);
-    b += 0x7fffu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xffff0000u);
-}
-
-// Local-memory barrier: orders this wavefront's LDS traffic with the other wavefronts' without
-// waiting for its global loads in flight (a full workgroup fence would drain them).
-__device__ __forceinline__ void lds_barrier() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
+using namespace attn;
 
 // 16-byte load from global memory proper (a pointer chosen between two arrays would otherwise be
 // loaded through the generic path, whose completion also counts as an LDS event).
@@ -121,19 +52,6 @@ __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& raw, uint4& first8,
     }
     first8 = make_uint4(o[0], o[1], o[2], o[3]);
     last8 = make_uint4(o[4], o[5], o[6], o[7]);
-}
-
-template <int V>
-struct IntC {
-    static constexpr int value = V;
-};
-// f(IntC<I>{}) for I = FROM .. TO-1, unrolled at compile time
-template <int FROM, int TO, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (FROM < TO) {
-        f(IntC<FROM>{});
-        static_for<FROM + 1, TO>(f);
-    }
 }
 
 // NW wavefronts, RB 32-row blocks per wavefront, KT keys per tile, KS key shares: with KS = 2 the
@@ -680,16 +598,16 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 }
             if (a.lse && g2 == 0) a.lse[rg_of[rb]] = m_ref[rb] * kLn2 + logf(l_tot);
         } else {
-            float* po = a.part_o + ((int64_t)split * rows_total + rg_of[rb]) * DH + 4 * g2;
+            // bf16 partial outputs, four values per 8-byte streaming store: the partials are read once, by the combine
+            // kernel, and leaving them dirty in L2 only lengthens the write-back at the end of this kernel
+            u32x2* po = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.part_o) + ((int64_t)split * rows_total + rg_of[rb]) * DH + 4 * g2);
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int vq = 0; vq < 4; ++vq)
-                {   // streaming store: the partials are read once, by another kernel, and leaving them
-                    // dirty in L2 only lengthens the write-back at the end of this one
-                    f32x4 val = {o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]};
-                    if constexpr (KV8) val *= v_unit;
-                    __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(po + 32 * db + 8 * vq));
+                for (int vq = 0; vq < 4; ++vq) {
+                    const u32x2 w = {pack_bf16x2(o[rb][db][4 * vq] * v_unit, o[rb][db][4 * vq + 1] * v_unit),
+                                     pack_bf16x2(o[rb][db][4 * vq + 2] * v_unit, o[rb][db][4 * vq + 3] * v_unit)};
+                    __builtin_nontemporal_store(w, po + 8 * db + 2 * vq);
                 }
             if (g2 == 0) {
                 float* pml = a.part_ml + ((int64_t)split * rows_total + rg_of[rb]) * 2;

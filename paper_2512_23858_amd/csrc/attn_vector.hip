@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(AttnArgs a) {
         }
     }
 
-    float* po = a.part_o + ((int64_t)split * rows + r) * DH + lane * EPL;
+    float* po = static_cast<float*>(a.part_o) + ((int64_t)split * rows + r) * DH + lane * EPL;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) po[e] = acc[e];
     if (lane == 0) {
@@ -154,7 +154,8 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(AttnArgs a) {
 // Splits are taken eight at a time with all of a group's loads issued before any is used, so a
 // row costs one memory round trip per group instead of one per split; groups are chained with the
 // usual running-maximum rescale.
-template <typename T, int DH>
+// PBF16: the partial outputs are bf16 (matrix-core kernels) instead of fp32 (vector kernel).
+template <typename T, int DH, bool PBF16>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     constexpr int TPR = DH / 4;  // threads per row
     constexpr int GS = 8;        // splits per group
@@ -172,7 +173,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
         for (int u = 0; u < GS; ++u) {
             const int s = min(s0 + u, nsp - 1);  // the tail repeats the last split; its weight is dropped below
             ml[u] = *reinterpret_cast<const float2*>(a.part_ml + ((int64_t)s * rows + r) * 2);
-            v[u] = *reinterpret_cast<const float4*>(a.part_o + ((int64_t)s * rows + r) * DH + c);
+            if constexpr (PBF16) {
+                const uint2 h = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a.part_o) + ((int64_t)s * rows + r) * DH + c);
+                v[u] = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xffff0000u),
+                                   __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xffff0000u));
+            } else {
+                v[u] = *reinterpret_cast<const float4*>(static_cast<const float*>(a.part_o) + ((int64_t)s * rows + r) * DH + c);
+            }
         }
         float mg = mstar;
 #pragma unroll
@@ -224,14 +231,15 @@ hipError_t launch_vector_t(const AttnArgs& a, const AttnPlan& p, hipStream_t st)
 }
 
 template <typename T>
-hipError_t launch_combine_t(const AttnArgs& a, hipStream_t st) {
+hipError_t launch_combine_t(const AttnArgs& a, bool partials_bf16, hipStream_t st) {
     const int64_t rows = (int64_t)a.B * a.N * a.Hq;
     if (a.Dh == 128) {
         dim3 grid((unsigned)((rows + 7) / 8));
-        hipLaunchKernelGGL((attn_combine_kernel<T, 128>), grid, dim3(256), 0, st, a);
+        if (partials_bf16) hipLaunchKernelGGL((attn_combine_kernel<T, 128, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((attn_combine_kernel<T, 128, false>), grid, dim3(256), 0, st, a);
     } else {
         dim3 grid((unsigned)((rows + 15) / 16));
-        hipLaunchKernelGGL((attn_combine_kernel<T, 64>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attn_combine_kernel<T, 64, false>), grid, dim3(256), 0, st, a);
     }
     return hipGetLastError();
 }
@@ -243,8 +251,7 @@ hipError_t launch_attn_vector(const AttnArgs& a, const AttnPlan& p, int dtype, h
 }
 
 hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st) {
-    (void)p;
-    return dtype == YGG_F32 ? launch_combine_t<float>(a, st) : launch_combine_t<uint16_t>(a, st);
+    return dtype == YGG_F32 ? launch_combine_t<float>(a, p.use_mfma != 0, st) : launch_combine_t<uint16_t>(a, p.use_mfma != 0, st);
 }
 
 }  // namespace ygg

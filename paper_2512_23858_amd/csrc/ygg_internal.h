@@ -10,6 +10,8 @@ namespace ygg {
 constexpr int kMaxNodes = 1024;      // N limit (ancestor bitmasks and per-tree tables live in LDS)
 constexpr int kMaxWidth = 64;        // W limit (one wavefront holds a candidate list)
 constexpr int kKeyTile = 64;         // split boundaries of the key range are multiples of this
+// Every workspace starts with a header of arrival counters (YGG_WORKSPACE_HEADER_BYTES): zero between calls.
+constexpr int kHeaderCounters = YGG_WORKSPACE_HEADER_BYTES / 4;
 
 // ---- tree attention ---------------------------------------------------------------------------
 // Key index space of sequence b: [0, L_b) are cache rows, [L_b, L_b + N) are the tree's own rows.
@@ -25,7 +27,7 @@ struct AttnArgs {
     const int32_t* parent_idx;
     const float* k_scale;  // [Hkv], both set: K and V hold 8-bit E4M3 codes; both null: plain elements
     const float* v_scale;
-    float* part_o;    // [nsplit][B*N*Hq][Dh]
+    void* part_o;     // [nsplit][B*N*Hq][Dh]: bf16 from the matrix-core kernels, fp32 from the vector kernel
     float* part_ml;   // [nsplit][B*N*Hq][2]   (running max m in scaled-score units, sum l)
     void* out;
     float* lse;
@@ -48,12 +50,14 @@ struct AttnPlan {
 AttnPlan plan_attention(const ygg_shape& s);
 hipError_t launch_attn_vector(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st);
+// dtype: element type of the output; partial outputs are bf16 when p.use_mfma, else fp32
 hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
 
 // One-time raising of the dynamic shared-memory limits of every kernel variant of a translation unit (current device).
 hipError_t raise_limits_attn_mfma();
 hipError_t raise_limits_expand();
 int32_t ensure_device_ready();
+hipError_t launch_zero_header(uint32_t* header, hipStream_t st);  // fill kernel (graph-capturable, unlike a memset node)
 
 // Measurement hook: when profiling is on, returns a fresh (start, stop) event pair for the next
 // attention main-kernel launch and true; otherwise false.
@@ -72,6 +76,7 @@ struct ExpandArgs {
     int32_t* parent_idx;
     int32_t* token_ids;
     float* cum_logprob;
+    uint32_t* counters;  // arrival counters (workspace header): [B] per sequence, then [B*F] per row
     void* stats;
     void* cands;
     void* offers;      // free attachment only: [B*F][W] {double score; int32 node; int32 token}
@@ -133,6 +138,7 @@ struct AcceptArgs {
     int32_t* accept_len;
     int32_t* accept_path;
     int32_t* bonus_token;
+    uint32_t* counters;  // arrival counters (workspace header): [B]
     void* part;
     int32_t* old_len;
     int32_t B, N, D, V, Hkv, Dh, n_layers, chunk, nchunk, max_seq_len;
