@@ -4,11 +4,13 @@
 One step = one pass of the whole path over one batch of synthetic input:
   D calls of ygg_equal_growth_expand, n_layers calls of ygg_tree_attention (one per layer, each
   layer with its own Q/K/V buffers), one call of ygg_accept_and_compact over all layers.
-Inputs are seeded, synthetic and already resident in HBM when the timed region starts.
+Inputs are seeded, synthetic and already resident in HBM when a timed region starts.  Steps are
+chained: acceptance advances seq_lens on the device and the next step starts from there, the way
+a decode loop runs (the caches are allocated with room for every step of a timed region).
 
-Prints ONE JSON line: the verify-step time per layer (whole step / n_layers), the roofline of the
-dominant kernel (tree attention, timed with dispatch-bound HIP events on its own stream) and the
-CPU oracle timed on a bounded sample of the same workload.
+With no --config the run covers the five workload configurations and prints ONE JSON line: the
+headline is the widest tree (configs[3]: step time per layer, roofline of the attention main
+kernel, CPU oracle on a bounded sample), `per_config` carries every configuration's figures.
 """
 from __future__ import annotations
 
@@ -23,9 +25,19 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 FP32_VALU_PEAK_TFLOPS = 157.3
+HEADLINE = 4                    # the widest tree: where the metric's matrix-core half lives
+ALL_CONFIGS = (1, 2, 3, 5, 4)   # headline last
+# layers per step when all configurations run: enough distinct K/V to exceed the 256 MB last-level cache
+DEFAULT_LAYERS = {1: 1, 2: 32, 3: 32, 4: 8, 5: 4}
+
+# HBM bytes per launch of the attention main kernel (FETCH_SIZE + WRITE_SIZE), measured offline with rocprofv3 --pmc
+# (a benchmark run cannot collect counters itself) by the commands in TRAFFIC_SOURCE, for the kernel as it stands in
+# the commit that file names.  Reported only together with that source.
+TRAFFIC_SOURCE = "profiles/attn_mfma_hbm_traffic.md"
+MEASURED_TRAFFIC_BYTES = {}
 
 
 def attention_work(cfg, lens, kv_bytes=None):
@@ -40,12 +52,6 @@ def attention_work(cfg, lens, kv_bytes=None):
     return nbytes, flops
 
 
-# HBM bytes per launch of the attention main kernel (fetched + written), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs
-# scaled by a streaming kernel of known size; a benchmark run cannot collect counters itself, so the figures measured with
-# the commands recorded in profiles/attn_mfma_hbm_traffic.md are carried here, per workload configuration.
-MEASURED_TRAFFIC_BYTES = {2: 26_075_033, 3: 37_865_267, 4: 177_698_509, 5: 329_497_497}
-
-
 def cpu_model():
     try:
         with open("/proc/cpuinfo") as f:
@@ -57,12 +63,292 @@ def cpu_model():
     return "unknown"
 
 
+def run_config(cid, args, want_cpu):
+    import torch
+    import paper_2512_23858_amd as ygg
+    import ygg_workloads as wl
+
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[cid]
+    variant = ""
+    if args.tree:
+        d_, w_ = (int(x) for x in args.tree.split(","))
+        cfg = wl.scaled(cfg, depth=d_, width=w_)
+        variant += f" with tree {d_}x{w_}"
+    if args.heads:
+        hq_, hkv_ = (int(x) for x in args.heads.split(","))
+        cfg = wl.scaled(cfg, n_q_heads=hq_, n_kv_heads=hkv_)
+        variant += f" with heads {hq_}/{hkv_}"
+    if args.prefix:
+        cfg = wl.scaled(cfg, prefix_len=args.prefix, prefix_range=())
+        variant += f" with prefix {args.prefix}"
+    if args.batch:
+        cfg = wl.scaled(cfg, batch=args.batch)
+        variant += f" with batch {args.batch}"
+    kv8 = args.kv == "fp8"
+    if kv8:
+        if cfg.dtype != "bf16" or cfg.head_dim != 128:
+            print("bench.py: --kv fp8 needs a bf16 configuration with head_dim 128", file=sys.stderr)
+            sys.exit(2)
+        variant += " with 8-bit K/V"
+    n_layers = args.layers or (cfg.n_layers if args.config else DEFAULT_LAYERS[cid])
+    B, N, D, W, V = cfg.batch, cfg.n_nodes, cfg.depth, cfg.width, cfg.vocab
+    Hkv, Dh = cfg.n_kv_heads, cfg.head_dim
+    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    # room for every chained step of the longest timed region (warm-up + K steps, or ten acceptance calls in a row)
+    chain = max(args.warmup + args.steps, 10) + 2
+    cap = cfg.max_prefix + chain * (D + 1)
+    max_seq_len = cap - (D + 1)
+
+    def up(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    # ---------------- inputs (host generator, then resident in HBM)
+    lens_h = wl.seq_lens(cfg)
+    parent_h = wl.trees(cfg)
+    token_h = wl.tokens(cfg, parent_h)
+    q = torch.empty((n_layers, B, N, cfg.n_q_heads, Dh), dtype=tdt, device=dev)
+    kvdt = torch.uint8 if kv8 else tdt
+    k_cache = torch.zeros((n_layers, B, cap, Hkv, Dh), dtype=kvdt, device=dev)
+    v_cache = torch.zeros_like(k_cache)
+    k_tree = torch.empty((n_layers, B, N, Hkv, Dh), dtype=kvdt, device=dev)
+    v_tree = torch.empty_like(k_tree)
+    k_scale = torch.ones((n_layers, Hkv), dtype=torch.float32, device=dev)
+    v_scale = torch.ones_like(k_scale)
+    layer0 = None
+    cap0 = cfg.kv_capacity
+    for layer in range(n_layers):
+        h = (wl.attention_inputs_fp8kv if kv8 else wl.attention_inputs)(cfg, layer=layer, lens=lens_h)
+        if layer == 0:
+            layer0 = h
+        q[layer] = up(h["q"])
+        k_cache[layer, :, :cap0], v_cache[layer, :, :cap0] = up(h["k_cache"]), up(h["v_cache"])
+        k_tree[layer], v_tree[layer] = up(h["k_tree"]), up(h["v_tree"])
+        if kv8:
+            k_scale[layer], v_scale[layer] = up(h["k_scale"]), up(h["v_scale"])
+    out = torch.empty_like(q)
+    draft_h = [wl.expansion_inputs(cfg, d) for d in range(1, D + 1)]
+    draft = [up(x) for x in draft_h]
+    target_h = wl.acceptance_inputs(cfg, parent_h, token_h)
+    target = up(target_h)
+    parent, token = up(parent_h), up(token_h)
+    lens0 = up(lens_h)
+    lens = lens0.clone()
+    e_parent = torch.full((B, N), -1, dtype=torch.int32, device=dev)
+    e_token = torch.zeros((B, N), dtype=torch.int32, device=dev)
+    e_cum = torch.zeros((B, N), dtype=torch.float32, device=dev)
+    accept_len = torch.zeros((B,), dtype=torch.int32, device=dev)
+    accept_path = torch.zeros((B, D + 1), dtype=torch.int32, device=dev)
+    bonus = torch.zeros((B,), dtype=torch.int32, device=dev)
+
+    shape = ygg.Shape(batch=B, n_q_heads=cfg.n_q_heads, n_kv_heads=Hkv, head_dim=Dh, depth=D, width=W, n_nodes=N,
+                      vocab=V, kv_dtype=2 if kv8 else 0 if cfg.dtype == "f32" else 1, softmax_scale=cfg.softmax_scale,
+                      kv_capacity=cap, max_seq_len=max_seq_len)
+    ws = [ygg.new_workspace(shape, op, n_layers, device=dev) for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT)]
+    ws_attach = pool = None
+    if args.growth == "attach":
+        ws_attach = ygg.new_workspace(shape, ygg.OP_ATTACH, device=dev)
+        pool = torch.empty(ygg.attach_pool_bytes(shape), dtype=torch.uint8, device=dev)
+
+    def attention_pass(main_kernel_only=False):
+        for layer in range(n_layers):
+            if kv8:
+                ygg.tree_attention_fp8kv(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer],
+                                         v_tree[layer], k_scale[layer], v_scale[layer], parent, out[layer], None, ws[0])
+            else:
+                ygg.tree_attention(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer], v_tree[layer],
+                                   parent, out[layer], None, ws[0], main_kernel_only=main_kernel_only)
+
+    def grow_all():
+        for d in range(1, D + 1):
+            if pool is None:
+                ygg.equal_growth_expand(shape, d, draft[d - 1], e_parent, e_token, e_cum, ws[1])
+            else:
+                ygg.equal_growth_attach(shape, d, draft[d - 1], e_parent, e_token, e_cum, pool, ws_attach)
+
+    def accept_call():
+        ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
+                               accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
+
+    def step():   # one decode step; seq_lens is left advanced for the next one
+        grow_all()
+        attention_pass()
+        accept_call()
+
+    def captured(fn):
+        if args.no_graph:
+            return fn
+        lens.copy_(lens0)   # the capture pass itself does not run anything, but warm-ups before it may have advanced
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g.replay
+
+    def timed(run, reps, reset=True):
+        """Mean and median of `reps` back-to-back runs, microseconds per run."""
+        if reset:
+            lens.copy_(lens0)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        torch.cuda.synchronize()
+        marks[0].record()
+        for i in range(reps):
+            run()
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        each = sorted(marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(reps))
+        return marks[0].elapsed_time(marks[reps]) * 1e3 / reps, each[reps // 2]
+
+    # ---------------- the whole step, chained K times (the driver's contract: W warm-up steps, exactly K timed)
+    body = attention_pass if args.attention_only else step
+    body()                # first launches (module load) stay outside the capture
+    torch.cuda.synchronize()
+    lens.copy_(lens0)
+    t_h = time.perf_counter()
+    body()
+    host_us = (time.perf_counter() - t_h) * 1e6   # host time to enqueue one step eagerly
+    torch.cuda.synchronize()
+    run_step = captured(body)
+    lens.copy_(lens0)
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step_us, step_us_median = timed(run_step, args.steps, reset=False)
+    wall_ms = (time.perf_counter() - t0) * 1e3
+
+    # ---------------- the calls on their own (graph replays; ten calls per replay for the short ones)
+    def many(fn, n):
+        def f():
+            for _ in range(n):
+                fn()
+        return f
+
+    nbytes, flops = attention_work(cfg, lens_h, kv_bytes=1 if kv8 else None)
+    att_us, _ = timed(captured(attention_pass), 10)
+    main_us = None
+    if not kv8:   # the hook times the bf16 / fp32 entry point's main kernel
+        main_us, _ = timed(captured(lambda: attention_pass(main_kernel_only=True)), 10)
+    kern_us = (main_us if main_us is not None else att_us) / n_layers
+    calls = None
+    if not args.attention_only:
+        grow_us, _ = timed(captured(many(grow_all, 10)), 10)
+        run_acc = captured(many(accept_call, 10))
+        acc_us = min(timed(run_acc, 1)[0] for _ in range(5))   # ten chained calls per replay, seq_lens reset between replays
+        w_keep = max(1, (3 * N) // 4)
+        p_kept = torch.zeros((B, w_keep), dtype=torch.int32, device=dev)
+        p_par, p_tok = torch.zeros_like(p_kept), torch.zeros_like(p_kept)
+        p_len = torch.zeros((B,), dtype=torch.float32, device=dev)
+        p_best = torch.zeros((B,), dtype=torch.int32, device=dev)
+        t_ver = torch.linspace(1.0, 2.0, N + 1, dtype=torch.float32, device=dev)
+
+        def prune_only():   # pruning of the tree the growth calls left in e_parent / e_token / e_cum
+            ygg.prune_for_verification(shape, w_keep, e_parent, e_token, e_cum, p_kept, p_par, p_tok, p_len, p_best,
+                                       t_verifier=t_ver, t_draft=1.0)
+        prune_us, _ = timed(captured(many(prune_only, 10)), 10)
+        grow_bytes = sum(int(x.numel()) * 4 for x in draft)   # every draft logit read once
+        acc_bytes = int(target.numel()) * 4                    # every target logit read once
+        calls = {"growth_us_per_draft_step": round(grow_us / 10 / D, 2),
+                 "growth_gbps": round(grow_bytes / (grow_us / 10 * 1e-6) / 1e9, 1),
+                 "accept_us_per_call": round(acc_us / 10, 2),
+                 "accept_argmax_gbps": round(acc_bytes / (acc_us / 10 * 1e-6) / 1e9, 1),
+                 "prune_us_per_call": round(prune_us / 10, 2), "prune_keeps": w_keep}
+
+    t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    ksec = kern_us * 1e-6
+    if cfg.dtype == "f32":
+        bound, peak, unit, ach = "alu", FP32_VALU_PEAK_TFLOPS, "TFLOP/s", flops / ksec / 1e12
+    elif t_mfma > t_hbm:
+        bound, peak, unit, ach = "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", flops / ksec / 1e12
+    else:
+        bound, peak, unit, ach = "hbm", HBM_PEAK_GBS, "GB/s", nbytes / ksec / 1e9
+    traffic = None if (variant or args.plan) else MEASURED_TRAFFIC_BYTES.get(cid)
+    roofline = {"bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
+                "traffic": traffic, "traffic_source": TRAFFIC_SOURCE if traffic is not None else None,
+                "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
+                "kernel_timing": "graph replay of the layers' main kernels back to back (ygg_debug_tree_attention_main), per launch",
+                "algorithmic_bytes": nbytes, "flops": flops,
+                "frac_of_hbm_peak": round(nbytes / ksec / 1e9 / HBM_PEAK_GBS, 4),
+                "frac_of_mfma_bf16_peak": None if cfg.dtype == "f32" else round(flops / ksec / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "gbps": round(nbytes / ksec / 1e9, 1), "tflops": round(flops / ksec / 1e12, 2)}
+
+    # ---------------- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if want_cpu:
+        import oracle
+        threads = oracle.max_threads()
+        rows_all = B * N * cfg.n_q_heads
+        # attention: a sample of output rows of layer 0 sized for a few seconds, scaled to all rows and layers
+        t = time.perf_counter()
+        probe = min(rows_all, 4 * threads)
+        rs = np.random.default_rng(0).choice(rows_all, size=probe, replace=False)
+        for r in rs:
+            b_, i_, h_ = r // (N * cfg.n_q_heads), (r // cfg.n_q_heads) % N, r % cfg.n_q_heads
+            if kv8:
+                oracle.attention_row_fp8kv(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                           layer0["v_tree"], layer0["k_scale"], layer0["v_scale"], parent_h,
+                                           cfg.softmax_scale, int(b_), int(i_), int(h_))
+            else:
+                oracle.attention_row(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                     layer0["v_tree"], parent_h, cfg.softmax_scale, int(b_), int(i_), int(h_))
+        per_row_serial = (time.perf_counter() - t) / probe
+        est_full = per_row_serial * rows_all / threads
+        if est_full <= 20.0:
+            t = time.perf_counter()
+            if kv8:
+                oracle.tree_attention_fp8kv(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                            layer0["v_tree"], layer0["k_scale"], layer0["v_scale"], parent_h,
+                                            cfg.softmax_scale)
+            else:
+                oracle.tree_attention(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
+                                      layer0["v_tree"], parent_h, cfg.softmax_scale)
+            t_attn_layer = time.perf_counter() - t
+            attn_note = "attention: all rows of layer 0 (OpenMP over rows)"
+        else:
+            t_attn_layer = est_full
+            attn_note = (f"attention: {probe} sampled rows of layer 0 run serially, scaled to {rows_all} rows "
+                         f"and {threads} threads")
+        p2 = np.full((B, N), -1, np.int32); t2 = np.zeros((B, N), np.int32); c2 = np.zeros((B, N), np.float32)
+        t = time.perf_counter()
+        for d in range(1, D + 1):
+            oracle.expand(D, W, d, draft_h[d - 1], p2, t2, c2)
+        t_expand = time.perf_counter() - t
+        kt1 = np.ascontiguousarray(layer0["k_tree"][None]); vt1 = np.ascontiguousarray(layer0["v_tree"][None])
+        kc1 = np.ascontiguousarray(layer0["k_cache"][None]); vc1 = np.ascontiguousarray(layer0["v_cache"][None])
+        t = time.perf_counter()
+        oracle.accept_compact(D + 1, parent_h, token_h, kt1, vt1, kc1, vc1, lens_h.copy(), target_logits=target_h)
+        t_accept = time.perf_counter() - t
+        cpu_step = n_layers * t_attn_layer if args.attention_only else t_expand + n_layers * t_attn_layer + t_accept
+        cpu = {"value": round(cpu_step / n_layers * 1e6, 1), "unit": "us/layer", "cores": threads, "cpu_model": cpu_model(),
+               "kind": "oracle",
+               "sample": f"{attn_note}; expansion: all {D} steps; acceptance: argmax+match+1-layer compaction; "
+                         f"step = expand + {n_layers} x attention layer + accept",
+               "attention_layer_s": round(t_attn_layer, 4), "expand_s": round(t_expand, 4), "accept_s": round(t_accept, 4)}
+
+    rec = {"workload": f"configs[{cid - 1}] {cfg.name}{variant}", "dtype": cfg.dtype, "layers": n_layers,
+           "us_per_layer": round(step_us / n_layers, 3), "decode_step_us": round(step_us, 2),
+           "decode_step_us_median": round(step_us_median, 2),
+           "attention_us_per_layer": round(att_us / n_layers, 3), "kernel_us": round(kern_us, 3),
+           "algorithmic_bytes": nbytes, "flops": flops, "bound": bound,
+           "frac_of_hbm_peak": roofline["frac_of_hbm_peak"], "frac_of_mfma_bf16_peak": roofline["frac_of_mfma_bf16_peak"],
+           "attention_plan": ygg.attention_plan(shape), "calls": calls,
+           "host_enqueue_us_per_step_eager": round(host_us, 1)}
+    detail = {"cfg": cfg, "n_layers": n_layers, "step_us": step_us, "step_us_median": step_us_median, "wall_ms": wall_ms,
+              "roofline": roofline, "cpu": cpu, "variant": variant, "kern_us": kern_us, "nbytes": nbytes, "flops": flops}
+    # release this configuration's buffers before the next one is generated
+    del q, k_cache, v_cache, k_tree, v_tree, out, draft, target
+    torch.cuda.empty_cache()
+    return rec, detail
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5")
+    ap.add_argument("--config", type=int, default=0, help="one workload configuration 1..5 (default: all five, headline configs[3])")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attention-only", action="store_true", help="time only the attention calls of a step")
@@ -88,321 +374,55 @@ def main():
 
     import torch
     import paper_2512_23858_amd as ygg
-    import ygg_workloads as wl
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     ygg.load_library()  # fails loudly if libygg.so is missing
+    ygg.init()
     if args.plan:
         ygg.set_attention_plan(*(int(x) for x in args.plan.split(",")))
-    dev = "cuda:0"
-    cfg = wl.CONFIGS[args.config]
-    variant = ""
-    if args.tree:
-        d_, w_ = (int(x) for x in args.tree.split(","))
-        cfg = wl.scaled(cfg, depth=d_, width=w_)
-        variant += f" with tree {d_}x{w_}"
-    if args.heads:
-        hq_, hkv_ = (int(x) for x in args.heads.split(","))
-        cfg = wl.scaled(cfg, n_q_heads=hq_, n_kv_heads=hkv_)
-        variant += f" with heads {hq_}/{hkv_}"
-    if args.prefix:
-        cfg = wl.scaled(cfg, prefix_len=args.prefix, prefix_range=())
-        variant += f" with prefix {args.prefix}"
-    if args.batch:
-        cfg = wl.scaled(cfg, batch=args.batch)
-        variant += f" with batch {args.batch}"
-    kv8 = args.kv == "fp8"
-    if kv8:
-        if cfg.dtype != "bf16" or cfg.head_dim != 128:
-            print("bench.py: --kv fp8 needs a bf16 configuration with head_dim 128", file=sys.stderr)
-            sys.exit(2)
-        variant += " with 8-bit K/V"
-    n_layers = args.layers or cfg.n_layers
-    B, N, D, W, V = cfg.batch, cfg.n_nodes, cfg.depth, cfg.width, cfg.vocab
-    Hkv, Dh, cap = cfg.n_kv_heads, cfg.head_dim, cfg.kv_capacity
-    tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
-
-    def up(a):
-        if a.dtype == np.uint16:
-            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
-        return torch.from_numpy(a).to(dev)
-
-    # ---------------- inputs (host generator, then resident in HBM)
-    lens_h = wl.seq_lens(cfg)
-    parent_h = wl.trees(cfg)
-    token_h = wl.tokens(cfg, parent_h)
-    q = torch.empty((n_layers, B, N, cfg.n_q_heads, Dh), dtype=tdt, device=dev)
-    kvdt = torch.uint8 if kv8 else tdt
-    k_cache = torch.empty((n_layers, B, cap, Hkv, Dh), dtype=kvdt, device=dev)
-    v_cache = torch.empty_like(k_cache)
-    k_tree = torch.empty((n_layers, B, N, Hkv, Dh), dtype=kvdt, device=dev)
-    v_tree = torch.empty_like(k_tree)
-    k_scale = torch.ones((n_layers, Hkv), dtype=torch.float32, device=dev)
-    v_scale = torch.ones_like(k_scale)
-    layer0 = None
-    for layer in range(n_layers):
-        h = (wl.attention_inputs_fp8kv if kv8 else wl.attention_inputs)(cfg, layer=layer, lens=lens_h)
-        if layer == 0:
-            layer0 = h
-        q[layer], k_cache[layer], v_cache[layer] = up(h["q"]), up(h["k_cache"]), up(h["v_cache"])
-        k_tree[layer], v_tree[layer] = up(h["k_tree"]), up(h["v_tree"])
-        if kv8:
-            k_scale[layer], v_scale[layer] = up(h["k_scale"]), up(h["v_scale"])
-    out = torch.empty_like(q)
-    draft_h = [wl.expansion_inputs(cfg, d) for d in range(1, D + 1)]
-    draft = [up(x) for x in draft_h]
-    target_h = wl.acceptance_inputs(cfg, parent_h, token_h)
-    target = up(target_h)
-    parent, token = up(parent_h), up(token_h)
-    lens0 = up(lens_h)
-    lens = lens0.clone()
-    e_parent = torch.full((B, N), -1, dtype=torch.int32, device=dev)
-    e_token = torch.zeros((B, N), dtype=torch.int32, device=dev)
-    e_cum = torch.zeros((B, N), dtype=torch.float32, device=dev)
-    accept_len = torch.zeros((B,), dtype=torch.int32, device=dev)
-    accept_path = torch.zeros((B, D + 1), dtype=torch.int32, device=dev)
-    bonus = torch.zeros((B,), dtype=torch.int32, device=dev)
-
-    shape = ygg.Shape(batch=B, n_q_heads=cfg.n_q_heads, n_kv_heads=Hkv, head_dim=Dh, depth=D, width=W, n_nodes=N,
-                      vocab=V, kv_dtype=2 if kv8 else 0 if cfg.dtype == "f32" else 1, softmax_scale=cfg.softmax_scale,
-                      kv_capacity=cap, max_seq_len=cfg.max_prefix)
-    ws = [ygg.new_workspace(shape, op, n_layers, device=dev) for op in (ygg.OP_ATTENTION, ygg.OP_EXPAND, ygg.OP_ACCEPT)]
-
-    ws_attach = pool = None
-    if args.growth == "attach":
-        ws_attach = ygg.new_workspace(shape, ygg.OP_ATTACH, device=dev)
-        pool = torch.empty(ygg.attach_pool_bytes(shape), dtype=torch.uint8, device=dev)
-
-    def attention_pass():
-        for layer in range(n_layers):
-            if kv8:
-                ygg.tree_attention_fp8kv(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer],
-                                         v_tree[layer], k_scale[layer], v_scale[layer], parent, out[layer], None, ws[0])
-            else:
-                ygg.tree_attention(shape, q[layer], k_cache[layer], v_cache[layer], lens, k_tree[layer], v_tree[layer],
-                                   parent, out[layer], None, ws[0])
-
-    def step():
-        lens.copy_(lens0)   # acceptance advances seq_lens; every step starts from the same state
-        for d in range(1, D + 1):
-            if pool is None:
-                ygg.equal_growth_expand(shape, d, draft[d - 1], e_parent, e_token, e_cum, ws[1])
-            else:
-                ygg.equal_growth_attach(shape, d, draft[d - 1], e_parent, e_token, e_cum, pool, ws_attach)
-        attention_pass()
-        ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
-                               accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
-
     if args.calibrate_copy:  # 256 MiB read + 256 MiB written by a plain elementwise kernel (dst = 2 * src)
-        src = torch.ones(256 * 1024 * 1024 // 4, dtype=torch.float32, device=dev)
+        src = torch.ones(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
         for _ in range(3):
             torch.mul(src, 2.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
 
-    body = attention_pass if args.attention_only else step
-    # All shapes are static and no call synchronises, so one step is captured once as a HIP graph and
-    # replayed: the timed region then holds the kernels of K whole steps and no per-launch host work.
-    eager_body = body
-    host_us_per_step = None
-    if not args.no_graph:
-        for _ in range(2):
-            eager_body()   # first launches (module load, kernel attributes) stay outside the capture
-        torch.cuda.synchronize()
-        t_h = time.perf_counter()
-        eager_body()
-        host_us_per_step = (time.perf_counter() - t_h) * 1e6  # host time to enqueue one step eagerly
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            eager_body()
-        body = graph.replay
-    for _ in range(args.warmup):
-        body()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for _ in range(args.steps):
-        body()
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    ms_per_step = ev0.elapsed_time(ev1) / args.steps
-    # the same K steps once more, each between its own pair of events: the median over steps, beside the mean above
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    marks[0].record()
-    for i in range(args.steps):
-        body()
-        marks[i + 1].record()
-    torch.cuda.synchronize()
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
-    ms_per_step_median = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
-
-    # ---------------- the three calls on their own (graph replays), with their algorithmic rates
-    def replay_us(fn, reps=20, inner=10):
-        # `inner` back-to-back calls per graph, so that the gap between two graph launches is not billed to a short call
-        def many():
-            for _ in range(inner):
-                fn()
-        if args.no_graph:
-            run = many
-        else:
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                many()
-            run = g.replay
-        for _ in range(3):
-            run()
-        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a0.record()
-        for _ in range(reps):
-            run()
-        a1.record()
-        torch.cuda.synchronize()
-        return a0.elapsed_time(a1) * 1e3 / (reps * inner)
-
-    def grow_all():
-        for d in range(1, D + 1):
-            if pool is None:
-                ygg.equal_growth_expand(shape, d, draft[d - 1], e_parent, e_token, e_cum, ws[1])
-            else:
-                ygg.equal_growth_attach(shape, d, draft[d - 1], e_parent, e_token, e_cum, pool, ws_attach)
-
-    def accept_only():
-        lens.copy_(lens0)
-        ygg.accept_and_compact(shape, n_layers, parent, token, k_tree, v_tree, k_cache, v_cache, lens,
-                               accept_len, accept_path, bonus, target_logits=target, workspace=ws[2])
-
-    w_keep = max(1, (3 * N) // 4)
-    p_kept = torch.zeros((B, w_keep), dtype=torch.int32, device=dev)
-    p_par, p_tok = torch.zeros_like(p_kept), torch.zeros_like(p_kept)
-    p_len = torch.zeros((B,), dtype=torch.float32, device=dev)
-    p_best = torch.zeros((B,), dtype=torch.int32, device=dev)
-    t_ver = torch.linspace(1.0, 2.0, N + 1, dtype=torch.float32, device=dev)
-
-    def prune_only():   # pruning of the tree the growth calls left in e_parent / e_token / e_cum
-        ygg.prune_for_verification(shape, w_keep, e_parent, e_token, e_cum, p_kept, p_par, p_tok, p_len, p_best,
-                                   t_verifier=t_ver, t_draft=1.0)
-
-    ops = None
-    if not args.attention_only:
-        grow_us = replay_us(grow_all)
-        acc_us = replay_us(accept_only)
-        att_us = replay_us(attention_pass, inner=1)
-        grow_bytes = sum(int(x.numel()) * 4 for x in draft)           # every draft logit read once
-        acc_bytes = int(target.numel()) * 4                            # every target logit read once
-        ops = {"growth_us_per_draft_step": round(grow_us / D, 2), "growth_gbps": round(grow_bytes / (grow_us * 1e-6) / 1e9, 1),
-               "accept_us_per_call": round(acc_us, 2), "accept_argmax_gbps": round(acc_bytes / (acc_us * 1e-6) / 1e9, 1),
-               "attention_us_per_layer": round(att_us / n_layers, 2),
-               "prune_us_per_call": round(replay_us(prune_only), 2), "prune_keeps": w_keep}
-
-    # ---------------- dominant kernel: same launches again with dispatch-bound events
-    ygg.profile_begin(args.steps * n_layers)
-    for _ in range(args.steps):
-        eager_body()
-    kern_us, kern_n = ygg.profile_end()
-    nbytes, flops = attention_work(cfg, lens_h, kv_bytes=1 if kv8 else None)
-    t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
-    if cfg.dtype == "f32":
-        bound, peak, unit, ach = "alu", FP32_VALU_PEAK_TFLOPS, "TFLOP/s", flops / (kern_us * 1e-6) / 1e12
-    elif flops / (MFMA_BF16_PEAK_TFLOPS * 1e12) > t_hbm:
-        bound, peak, unit, ach = "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s", flops / (kern_us * 1e-6) / 1e12
-    else:
-        bound, peak, unit, ach = "hbm", HBM_PEAK_GBS, "GB/s", nbytes / (kern_us * 1e-6) / 1e9
-    roofline = {"bound": bound, "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
-                "traffic": None if variant else MEASURED_TRAFFIC_BYTES.get(args.config), "kernel": "tree attention main kernel", "kernel_us": round(kern_us, 3),
-                "launches_timed": kern_n, "algorithmic_bytes": nbytes, "flops": flops,
-                "frac_of_hbm_peak": round(nbytes / (kern_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                "frac_of_mfma_bf16_peak": None if cfg.dtype == "f32" else round(flops / (kern_us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                "gbps": round(nbytes / (kern_us * 1e-6) / 1e9, 1), "tflops": round(flops / (kern_us * 1e-6) / 1e12, 2)}
-
-    # ---------------- CPU oracle on a bounded sample of the same workload
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        rows_all = B * N * cfg.n_q_heads
-        # attention: time a sample of output rows of layer 0 sized for roughly 10 s, scale to all rows and layers
-        t = time.perf_counter()
-        probe = min(rows_all, 4 * threads)
-        rs = np.random.default_rng(0).choice(rows_all, size=probe, replace=False)
-        def run_rows(sel):
-            # the oracle's full routine parallelises over rows; sampled rows go through the row routine
-            for r in sel:
-                b_, i_, h_ = r // (N * cfg.n_q_heads), (r // cfg.n_q_heads) % N, r % cfg.n_q_heads
-                if kv8:
-                    oracle.attention_row_fp8kv(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
-                                               layer0["v_tree"], layer0["k_scale"], layer0["v_scale"], parent_h,
-                                               cfg.softmax_scale, int(b_), int(i_), int(h_))
-                else:
-                    oracle.attention_row(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
-                                         layer0["v_tree"], parent_h, cfg.softmax_scale, int(b_), int(i_), int(h_))
-        run_rows(rs)
-        per_row_serial = (time.perf_counter() - t) / probe
-        est_full = per_row_serial * rows_all / threads
-        if est_full <= 20.0:
-            t = time.perf_counter()
-            if kv8:
-                oracle.tree_attention_fp8kv(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
-                                            layer0["v_tree"], layer0["k_scale"], layer0["v_scale"], parent_h,
-                                            cfg.softmax_scale)
-            else:
-                oracle.tree_attention(layer0["q"], layer0["k_cache"], layer0["v_cache"], lens_h, layer0["k_tree"],
-                                      layer0["v_tree"], parent_h, cfg.softmax_scale)
-            t_attn_layer = time.perf_counter() - t
-            attn_note = "attention: all rows of layer 0 (OpenMP over rows)"
-        else:
-            t_attn_layer = est_full
-            attn_note = (f"attention: {probe} sampled rows of layer 0 run serially, scaled to {rows_all} rows "
-                         f"and {threads} threads")
-        # expansion: all D steps; acceptance: argmax + match + compaction of one layer
-        p2 = np.full((B, N), -1, np.int32); t2 = np.zeros((B, N), np.int32); c2 = np.zeros((B, N), np.float32)
-        t = time.perf_counter()
-        for d in range(1, D + 1):
-            oracle.expand(D, W, d, draft_h[d - 1], p2, t2, c2)
-        t_expand = time.perf_counter() - t
-        kt1 = np.ascontiguousarray(layer0["k_tree"][None]); vt1 = np.ascontiguousarray(layer0["v_tree"][None])
-        kc1 = np.ascontiguousarray(layer0["k_cache"][None]); vc1 = np.ascontiguousarray(layer0["v_cache"][None])
-        t = time.perf_counter()
-        oracle.accept_compact(D + 1, parent_h, token_h, kt1, vt1, kc1, vc1, lens_h.copy(), target_logits=target_h)
-        t_accept = time.perf_counter() - t
-        if args.attention_only:
-            cpu_step = n_layers * t_attn_layer
-        else:
-            cpu_step = t_expand + n_layers * t_attn_layer + t_accept
-        cpu = {"value": round(cpu_step / n_layers * 1e6, 1), "unit": "us/layer", "cores": threads, "cpu_model": cpu_model(), "kind": "oracle",
-               "sample": f"{attn_note}; expansion: all {D} steps; acceptance: argmax+match+1-layer compaction; "
-                         f"step = expand + {n_layers} x attention layer + accept",
-               "attention_layer_s": round(t_attn_layer, 4), "expand_s": round(t_expand, 4),
-               "accept_s": round(t_accept, 4)}
-
-    rec = {
+    ids = (args.config,) if args.config else ALL_CONFIGS
+    head_id = args.config or HEADLINE
+    per_config, head = [], None
+    for cid in ids:
+        rec, detail = run_config(cid, args, want_cpu=(cid == head_id and not args.no_cpu_baseline))
+        per_config.append(rec)
+        if cid == head_id:
+            head = (rec, detail)
+    rec, d = head
+    cfg = d["cfg"]
+    ksec = d["kern_us"] * 1e-6
+    out = {
         # the headline metric's first part is `value`; its second part (achieved HBM TB/s and MFMA % of the attention
-        # main kernel) is spelled out in the two fields after `unit` and in `roofline`
+        # main kernel) is spelled out in the two fields after `unit`, in `roofline`, and per configuration in `per_config`
         "metric": "verify-step µs per layer + achieved HBM TB/s and MFMA % for tree attention",
-        "value": round(ms_per_step * 1e3 / n_layers, 3), "unit": "µs/layer",
-        "value_definition": "one whole verification step (D growth calls + `layers` attention calls + accept/compact) divided by layers",
-        "attention_hbm_tb_s": round(nbytes / (kern_us * 1e-6) / 1e12, 3),
-        "attention_mfma_pct_of_bf16_dense_peak": None if cfg.dtype == "f32" else round(100 * flops / (kern_us * 1e-6) / (MFMA_BF16_PEAK_TFLOPS * 1e12), 2),
-        "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "ms_per_step_median": round(ms_per_step_median, 5), "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}] {cfg.name}{variant}", "batch": B, "q_heads": cfg.n_q_heads,
-                   "kv_heads": Hkv, "head_dim": Dh, "prefix": cfg.prefix_len or list(cfg.prefix_range),
-                   "tree": f"depth {D} x width {W} + root = {N} nodes", "vocab": V, "layers": n_layers,
-                   "scope": "attention only" if args.attention_only else "full step"},
-        "wall_ms_timed_region": round(wall_ms, 2),
+        "value": rec["us_per_layer"], "unit": "µs/layer",
+        "value_definition": "one whole verification step (D growth calls + `layers` attention calls + accept/compact), chained "
+                            "on the device, divided by layers",
+        "attention_hbm_tb_s": round(d["nbytes"] / ksec / 1e12, 3),
+        "attention_mfma_pct_of_bf16_dense_peak": None if cfg.dtype == "f32" else round(100 * d["flops"] / ksec / (MFMA_BF16_PEAK_TFLOPS * 1e12), 2),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(d["step_us"] * 1e-3, 5), "ms_per_step_median": round(d["step_us_median"] * 1e-3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": rec["workload"], "batch": cfg.batch, "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads,
+                   "head_dim": cfg.head_dim, "prefix": cfg.prefix_len or list(cfg.prefix_range),
+                   "tree": f"depth {cfg.depth} x width {cfg.width} + root = {cfg.n_nodes} nodes", "vocab": cfg.vocab,
+                   "layers": d["n_layers"], "scope": "attention only" if args.attention_only else "full step"},
+        "wall_ms_timed_region": round(d["wall_ms"], 2),
         "growth": args.growth,
-        "calls": ops,
         "launch": "eager" if args.no_graph else "hip-graph replay of one captured step",
-        "host_enqueue_us_per_step_eager": None if host_us_per_step is None else round(host_us_per_step, 1),
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": d["roofline"], "cpu_baseline": d["cpu"], "per_config": per_config,
     }
-    print(json.dumps(rec))
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":

@@ -304,16 +304,16 @@ int32_t ygg_debug_attention_plan(const ygg_shape *shape, int32_t *plan /* [5], h
 int32_t ygg_debug_set_attention_plan(int32_t waves, int32_t rblocks, int32_t nsplit, int32_t kshares);
 
 /*
- * Measurement hook for benchmarks (not part of the verification path; not thread-safe).
- * Between ygg_profile_begin and ygg_profile_end every launch of the tree-attention main kernel
- * is bracketed by a pair of HIP events bound to that dispatch (hipExtLaunchKernelGGL), so the
- * elapsed time of a pair is the kernel's own execution time on the stream it ran on, without
- * launch gaps.  ygg_profile_end synchronises the device, writes the average duration in
- * microseconds and the number of launches seen (launches beyond max_launches are not timed),
- * and releases the events.  Only host-side event objects are created; no device memory.
+ * Measurement hook for benchmarks (not part of the verification path): ygg_tree_attention without the launch that
+ * merges the key splits, i.e. the main kernel alone, enqueued like any other call.  `out` and `lse` are only
+ * complete for shapes with a single key split.  Timing a captured sequence of such calls gives the main kernel's
+ * duration without event pairs, host gaps or library state.  Same arguments and errors as ygg_tree_attention.
  */
-int32_t ygg_profile_begin(int32_t max_launches);
-int32_t ygg_profile_end(double *avg_us, int32_t *n_launches);
+int32_t ygg_debug_tree_attention_main(const ygg_shape *shape,
+                                      const void *q, const void *k_cache, const void *v_cache,
+                                      const int32_t *seq_lens, const void *k_tree, const void *v_tree,
+                                      const int32_t *parent_idx, void *out, float *lse,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

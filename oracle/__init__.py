@@ -53,6 +53,13 @@ def _load():
     return _lib
 
 
+def max_threads() -> int:
+    """Threads the oracle's row-parallel loops run on (OpenMP's maximum for this process)."""
+    lib = _load()
+    lib.ygg_oracle_max_threads.restype = ctypes.c_int
+    return int(lib.ygg_oracle_max_threads())
+
+
 def _dtype_code(a: np.ndarray) -> int:
     if a.dtype == np.float32:
         return F32

@@ -41,6 +41,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_FP8_E4M3 = 2 };
 
@@ -849,4 +852,14 @@ int ygg_oracle_validate(int32_t B, int32_t N, int32_t depth, int32_t vocab, int3
     }
     free(dep);
     return 0;
+}
+
+/* Number of threads the row-parallel loops above use (for the benchmark's CPU-baseline record; no arithmetic). */
+int ygg_oracle_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }

@@ -16,8 +16,6 @@ from .binding import (  # noqa: F401
     lib_path,
     load_library,
     new_workspace,
-    profile_begin,
-    profile_end,
     prune_for_verification,
     set_attention_plan,
     status_string,

@@ -95,10 +95,8 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_debug_set_attention_plan.argtypes = [i32, i32, i32, i32]
         lib.ygg_debug_attention_plan.restype = i32
         lib.ygg_debug_attention_plan.argtypes = [shp, ctypes.POINTER(i32)]
-        lib.ygg_profile_begin.restype = i32
-        lib.ygg_profile_begin.argtypes = [i32]
-        lib.ygg_profile_end.restype = i32
-        lib.ygg_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+        lib.ygg_debug_tree_attention_main.restype = i32
+        lib.ygg_debug_tree_attention_main.argtypes = [shp] + [vp] * 9 + [vp, sz, vp]
         _lib = lib
     return _lib
 
@@ -160,12 +158,14 @@ def _ws(workspace):
 
 
 def tree_attention(shape: Shape, q, k_cache, v_cache, seq_lens, k_tree, v_tree, parent_idx, out, lse=None,
-                   workspace=None):
-    """ygg_tree_attention: writes `out` (and `lse` if given) on the current stream."""
+                   workspace=None, main_kernel_only=False):
+    """ygg_tree_attention: writes `out` (and `lse` if given) on the current stream.
+    main_kernel_only: the measurement hook ygg_debug_tree_attention_main (no merge of the key splits)."""
     dt = _kv_torch_dtype(shape)
     cs = shape.c()
     wsp, wsn = _ws(workspace)
-    rc = load_library().ygg_tree_attention(
+    fn = load_library().ygg_debug_tree_attention_main if main_kernel_only else load_library().ygg_tree_attention
+    rc = fn(
         ctypes.byref(cs), _dev(q, dt, "q"), _dev(k_cache, dt, "k_cache"), _dev(v_cache, dt, "v_cache"),
         _dev(seq_lens, torch.int32, "seq_lens"), _dev(k_tree, dt, "k_tree"), _dev(v_tree, dt, "v_tree"),
         _dev(parent_idx, torch.int32, "parent_idx"), _dev(out, dt, "out"), _dev(lse, torch.float32, "lse"),
@@ -276,15 +276,3 @@ def init():
 def set_attention_plan(waves: int = 0, rblocks: int = 0, nsplit: int = 0, kshares: int = 0):
     """ygg_debug_set_attention_plan: tuning override of the attention launch plan (all zero: none)."""
     _check(load_library().ygg_debug_set_attention_plan(waves, rblocks, nsplit, kshares), "ygg_debug_set_attention_plan")
-
-
-def profile_begin(max_launches: int):
-    """Measurement hook: time every attention main-kernel launch until profile_end()."""
-    _check(load_library().ygg_profile_begin(max_launches), "ygg_profile_begin")
-
-
-def profile_end():
-    """Returns (average kernel duration in microseconds, number of launches timed)."""
-    avg, n = ctypes.c_double(0.0), ctypes.c_int32(0)
-    _check(load_library().ygg_profile_end(ctypes.byref(avg), ctypes.byref(n)), "ygg_profile_end")
-    return avg.value, n.value

@@ -23,8 +23,6 @@
 // wavefronts widen the codes to bf16 while filling the LDS tiles, everything else is shared.
 #include "attn_common.h"
 
-#include <hip/hip_ext.h>
-
 #include <cstdlib>
 #include <type_traits>
 
@@ -640,11 +638,7 @@ hipError_t launch_variant(const AttnArgs& a, const AttnPlan& p, hipStream_t st) 
     auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8, NT>;
     const unsigned threads = (NW + (KV8 ? 4 : 0)) * 64;  // KV8: plus the four loading wavefronts
     if (smem > kMaxSmem) return hipErrorInvalidValue;  // cannot happen for N <= 1024: checked again for the sake of the launch
-    hipEvent_t ev0, ev1;
-    if (profile_next_events(&ev0, &ev1))
-        hipExtLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), (uint32_t)smem, st, ev0, ev1, 0, a, RT, S);
-    else
-        hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), smem, st, a, RT, S);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), smem, st, a, RT, S);
     return hipGetLastError();
 }
 

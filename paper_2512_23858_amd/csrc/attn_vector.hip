@@ -218,15 +218,8 @@ template <typename T>
 hipError_t launch_vector_t(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int64_t rows = (int64_t)a.B * a.N * a.Hq;
     dim3 grid((unsigned)((rows + 3) / 4), (unsigned)p.nsplit);
-    hipEvent_t ev0, ev1;
-    const bool timed = profile_next_events(&ev0, &ev1);
-    if (a.Dh == 128) {
-        if (timed) hipExtLaunchKernelGGL((attn_vector_kernel<T, 128>), grid, dim3(256), 0, st, ev0, ev1, 0, a);
-        else hipLaunchKernelGGL((attn_vector_kernel<T, 128>), grid, dim3(256), 0, st, a);
-    } else {
-        if (timed) hipExtLaunchKernelGGL((attn_vector_kernel<T, 64>), grid, dim3(256), 0, st, ev0, ev1, 0, a);
-        else hipLaunchKernelGGL((attn_vector_kernel<T, 64>), grid, dim3(256), 0, st, a);
-    }
+    if (a.Dh == 128) hipLaunchKernelGGL((attn_vector_kernel<T, 128>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((attn_vector_kernel<T, 64>), grid, dim3(256), 0, st, a);
     return hipGetLastError();
 }
 

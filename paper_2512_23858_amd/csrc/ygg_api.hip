@@ -5,16 +5,9 @@
 #include <atomic>
 #include <cmath>
 #include <mutex>
-#include <vector>
 
 namespace ygg {
 namespace {
-
-struct ProfileState {
-    bool on = false;
-    size_t used = 0;
-    std::vector<hipEvent_t> start, stop;
-} g_profile;
 
 // Launch-plan override for tuning runs (ygg_debug_set_attention_plan): waves << 24 | rblocks << 16 | kshares << 8 in the
 // upper word, the forced split count in the lower; 0 = no override.
@@ -122,14 +115,6 @@ AttnPlan plan_attention(const ygg_shape& s) {
     return p;
 }
 
-bool profile_next_events(hipEvent_t* start, hipEvent_t* stop) {
-    if (!g_profile.on || g_profile.used >= g_profile.start.size()) return false;
-    *start = g_profile.start[g_profile.used];
-    *stop = g_profile.stop[g_profile.used];
-    ++g_profile.used;
-    return true;
-}
-
 // Raises the shared-memory limits of the current device's kernels once; later calls cost one atomic load.
 int32_t ensure_device_ready() {
     int dev = 0;
@@ -169,41 +154,6 @@ int32_t ygg_debug_attention_plan(const ygg_shape* s, int32_t* plan) {
     const AttnPlan p = plan_attention(*s);
     plan[0] = p.use_mfma; plan[1] = p.waves; plan[2] = p.kshares; plan[3] = p.row_tiles; plan[4] = p.nsplit;
     return YGG_OK;
-}
-
-int32_t ygg_profile_begin(int32_t max_launches) {
-    if (max_launches < 1 || g_profile.on) return YGG_ERR_SHAPE;
-    g_profile.start.resize((size_t)max_launches);
-    g_profile.stop.resize((size_t)max_launches);
-    for (int32_t i = 0; i < max_launches; ++i) {
-        if (hipEventCreate(&g_profile.start[i]) != hipSuccess || hipEventCreate(&g_profile.stop[i]) != hipSuccess)
-            return YGG_ERR_LAUNCH;
-    }
-    g_profile.used = 0;
-    g_profile.on = true;
-    return YGG_OK;
-}
-
-int32_t ygg_profile_end(double* avg_us, int32_t* n_launches) {
-    if (!g_profile.on) return YGG_ERR_SHAPE;
-    g_profile.on = false;
-    int32_t rc = hipDeviceSynchronize() == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
-    double total_ms = 0.0;
-    for (size_t i = 0; i < g_profile.used && rc == YGG_OK; ++i) {
-        float ms = 0.f;
-        if (hipEventElapsedTime(&ms, g_profile.start[i], g_profile.stop[i]) != hipSuccess) rc = YGG_ERR_LAUNCH;
-        total_ms += ms;
-    }
-    if (avg_us) *avg_us = g_profile.used ? total_ms * 1000.0 / (double)g_profile.used : 0.0;
-    if (n_launches) *n_launches = (int32_t)g_profile.used;
-    for (size_t i = 0; i < g_profile.start.size(); ++i) {
-        (void)hipEventDestroy(g_profile.start[i]);
-        (void)hipEventDestroy(g_profile.stop[i]);
-    }
-    g_profile.start.clear();
-    g_profile.stop.clear();
-    g_profile.used = 0;
-    return rc;
 }
 
 const char* ygg_status_string(int32_t status) {
@@ -250,7 +200,7 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
                                    const int32_t* seq_lens, const void* k_tree, const void* v_tree,
                                    const float* k_scale, const float* v_scale,
                                    const int32_t* parent_idx, void* out, float* lse, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream) {
+                                   size_t workspace_bytes, void* hip_stream, bool main_only = false) {
     if (!q || !k_tree || !v_tree || !seq_lens || !parent_idx || !out) return YGG_ERR_NULL;
     if (s->max_seq_len > 0 && (!k_cache || !v_cache)) return YGG_ERR_NULL;
     // the kernels index query rows with 31 bits and address one sequence's K/V slab with 32-bit byte offsets
@@ -275,6 +225,7 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     const int out_dtype = s->kv_dtype == YGG_F32 ? YGG_F32 : YGG_BF16;  // element type of Q and O
     hipError_t e = p.use_mfma ? launch_attn_mfma(a, p, st) : launch_attn_vector(a, p, s->kv_dtype, st);
     if (e != hipSuccess) return YGG_ERR_LAUNCH;
+    if (main_only) return YGG_OK;
     if (p.use_mfma && p.nsplit == 1) return YGG_OK;  // the kernel wrote the final rows itself
     e = launch_attn_combine(a, p, out_dtype, st);
     return e == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
@@ -288,6 +239,16 @@ int32_t ygg_tree_attention(const ygg_shape* s, const void* q, const void* k_cach
     if (s->kv_dtype == YGG_FP8_E4M3) return YGG_ERR_UNSUPPORTED;  // codes need their scales: ygg_tree_attention_fp8kv
     return tree_attention_impl(s, q, k_cache, v_cache, seq_lens, k_tree, v_tree, nullptr, nullptr, parent_idx, out, lse,
                                workspace, workspace_bytes, hip_stream);
+}
+
+int32_t ygg_debug_tree_attention_main(const ygg_shape* s, const void* q, const void* k_cache, const void* v_cache,
+                                      const int32_t* seq_lens, const void* k_tree, const void* v_tree,
+                                      const int32_t* parent_idx, void* out, float* lse, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+    if (int32_t rc = check_shape(s, true, false)) return rc;
+    if (s->kv_dtype == YGG_FP8_E4M3) return YGG_ERR_UNSUPPORTED;
+    return tree_attention_impl(s, q, k_cache, v_cache, seq_lens, k_tree, v_tree, nullptr, nullptr, parent_idx, out, lse,
+                               workspace, workspace_bytes, hip_stream, /*main_only=*/true);
 }
 
 int32_t ygg_tree_attention_fp8kv(const ygg_shape* s, const void* q, const void* k_cache, const void* v_cache,

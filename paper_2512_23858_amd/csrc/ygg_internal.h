@@ -59,10 +59,6 @@ hipError_t raise_limits_expand();
 int32_t ensure_device_ready();
 hipError_t launch_zero_header(uint32_t* header, hipStream_t st);  // fill kernel (graph-capturable, unlike a memset node)
 
-// Measurement hook: when profiling is on, returns a fresh (start, stop) event pair for the next
-// attention main-kernel launch and true; otherwise false.
-bool profile_next_events(hipEvent_t* start, hipEvent_t* stop);
-
 // ---- equal-growth expansion -------------------------------------------------------------------
 struct ExpandPlan {
     int32_t F;            // frontier rows
