@@ -182,6 +182,20 @@ int32_t ygg_equal_growth_expand(const ygg_shape *shape, int32_t d, const float *
                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * ygg_equal_growth_expand for callers that cannot allocate or carry a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Same operation, same kernels, same results; the
+ * scratch is a fixed array inside the library's device image (YGG_STATIC_SCRATCH_BYTES per GPU, held until the
+ * process ends), so the call allocates nothing and takes no workspace argument.  Shapes whose
+ * ygg_workspace_bytes(shape, YGG_OP_EXPAND) exceeds YGG_STATIC_SCRATCH_BYTES are rejected with
+ * YGG_ERR_WORKSPACE.  All calls on one GPU share that array: calls that may overlap on one GPU (different
+ * streams, concurrent graphs) race and must use ygg_equal_growth_expand with workspaces of their own.
+ */
+#define YGG_STATIC_SCRATCH_BYTES (4u << 20)
+int32_t ygg_equal_growth_expand_static(const ygg_shape *shape, int32_t d, const float *draft_logits,
+                                       int32_t *parent_idx, int32_t *token_ids, float *cum_logprob,
+                                       void *hip_stream);
+
+/*
  * Equal growth with free attachment: draft step t (1..D) of the Equal-Growth Tree as the paper words
  * it (Sec. 4.2 "Draft Width Selection": every step grows exactly W_draft leaves, and they may hang
  * anywhere in the partial tree, at the positions with the largest path-wise gain).  Reading: every

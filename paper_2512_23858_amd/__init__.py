@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     debug_validate,
     equal_growth_attach,
     equal_growth_expand,
+    equal_growth_expand_static,
     init,
     lib_path,
     load_library,

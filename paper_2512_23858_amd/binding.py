@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_tree_attention_fp8kv.argtypes = [shp] + [vp] * 11 + [vp, sz, vp]
         lib.ygg_equal_growth_expand.restype = i32
         lib.ygg_equal_growth_expand.argtypes = [shp, i32] + [vp] * 4 + [vp, sz, vp]
+        lib.ygg_equal_growth_expand_static.restype = i32
+        lib.ygg_equal_growth_expand_static.argtypes = [shp, i32] + [vp] * 4 + [vp]
         lib.ygg_attach_pool_bytes.restype = sz
         lib.ygg_attach_pool_bytes.argtypes = [shp]
         lib.ygg_equal_growth_attach.restype = i32
@@ -199,6 +201,16 @@ def equal_growth_expand(shape: Shape, d: int, draft_logits, parent_idx, token_id
         _dev(parent_idx, torch.int32, "parent_idx"), _dev(token_ids, torch.int32, "token_ids"),
         _dev(cum_logprob, torch.float32, "cum_logprob"), wsp, wsn, _stream())
     _check(rc, "ygg_equal_growth_expand")
+
+
+def equal_growth_expand_static(shape: Shape, d: int, draft_logits, parent_idx, token_ids, cum_logprob):
+    """ygg_equal_growth_expand_static: the same draft step on the library's built-in scratch (no workspace)."""
+    cs = shape.c()
+    rc = load_library().ygg_equal_growth_expand_static(
+        ctypes.byref(cs), d, _dev(draft_logits, torch.float32, "draft_logits"),
+        _dev(parent_idx, torch.int32, "parent_idx"), _dev(token_ids, torch.int32, "token_ids"),
+        _dev(cum_logprob, torch.float32, "cum_logprob"), _stream())
+    _check(rc, "ygg_equal_growth_expand_static")
 
 
 def attach_pool_bytes(shape: Shape) -> int:

@@ -19,6 +19,13 @@ constexpr int kMaxDevices = 64;
 std::atomic<bool> g_device_ready[kMaxDevices];
 std::mutex g_init_mutex;
 
+// Library-owned workspace of ygg_equal_growth_expand_static, for callers that cannot provide one.  Every device
+// holds its own copy at its own address (looked up once per device, below); host code only ever uses that
+// address.  Zero at load, and every call leaves the header of arrival counters zero again.
+constexpr size_t kStaticScratchBytes = YGG_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+unsigned char* g_scratch_ptr[kMaxDevices];
+
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 constexpr size_t kHeaderBytes = YGG_WORKSPACE_HEADER_BYTES;
 
@@ -123,6 +130,9 @@ int32_t ensure_device_ready() {
     std::lock_guard<std::mutex> lock(g_init_mutex);
     if (g_device_ready[dev].load(std::memory_order_relaxed)) return YGG_OK;
     if (raise_limits_attn_mfma() != hipSuccess || raise_limits_expand() != hipSuccess) return YGG_ERR_LAUNCH;
+    void* sp = nullptr;
+    if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) return YGG_ERR_LAUNCH;
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(sp);
     g_device_ready[dev].store(true, std::memory_order_release);
     return YGG_OK;
 }
@@ -286,6 +296,17 @@ int32_t ygg_equal_growth_expand(const ygg_shape* s, int32_t d, const float* draf
     a.B = s->batch; a.D = s->depth; a.W = s->width; a.V = s->vocab; a.N = s->n_nodes; a.d = d;
     a.F = p.F; a.chunk = p.chunk; a.nchunk = p.nchunk;
     return launch_expand(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
+}
+
+int32_t ygg_equal_growth_expand_static(const ygg_shape* s, int32_t d, const float* draft_logits, int32_t* parent_idx,
+                                       int32_t* token_ids, float* cum_logprob, void* hip_stream) {
+    const size_t need = ygg_workspace_bytes(s, YGG_OP_EXPAND, 0);
+    if (need > kStaticScratchBytes) return YGG_ERR_WORKSPACE;   // shape too large for the built-in scratch (0: invalid shape, reported below)
+    if (int32_t rc = ensure_device_ready()) return rc;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices || !g_scratch_ptr[dev]) return YGG_ERR_LAUNCH;
+    return ygg_equal_growth_expand(s, d, draft_logits, parent_idx, token_ids, cum_logprob, g_scratch_ptr[dev],
+                                   kStaticScratchBytes, hip_stream);
 }
 
 size_t ygg_attach_pool_bytes(const ygg_shape* s) {
