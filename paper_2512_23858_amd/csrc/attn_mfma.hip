@@ -67,8 +67,12 @@ __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& raw, uint4& first8,
 //
 // NT: the direct-to-LDS tile fills carry the streaming hint (the host sets it when a K/V stream has one
 // row tile, i.e. is read by a single workgroup; with several row tiles the re-reads are meant to hit in L2).
-template <int NW, int RB, int KT, int KS, bool KV8, bool NT>
+//
+// BAL: balanced batches (see the segment loop below); a separate instantiation, so that the single-segment variants
+// carry none of its loop state.
+template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false>
 __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
+    static_assert(!BAL || (KS == 1 && !KV8), "balanced batches: plain 32-row wavefronts only");
     static_assert(KS == 1 || (KS == 2 && NW % 2 == 0 && KT == 64), "key shares: one block of the tile each");
     constexpr int NLD = KV8 ? 4 : 0;                             // loading wavefronts (KV8 only)
     constexpr int NSET = 4;                                      // register sets (tiles in flight) per loader
@@ -99,20 +103,98 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     const int rt = (wg >> 3) % RT;
     const int sigma = (wg / (8 * RT)) * 8 + xcd;
     if (sigma >= S) return;
-    const int split = sigma % a.nsplit;
-    const int hk = (sigma / a.nsplit) % a.Hkv;
-    const int b = sigma / (a.nsplit * a.Hkv);
-
     const int R = a.N * a.G;
     const int row_base = rt * RW;
+    const int64_t rows_total = (int64_t)a.B * a.N * a.Hq;
+
+    // Which (sequence, key range) segments does this workgroup serve?
+    //   classic   one segment: sigma = (sequence, kv head, split); the split is one of nsplit equal chunks of that
+    //             sequence's own key range.
+    //   balanced  (a.slots > 0, batches) sigma = (kv head, slot).  The sequences' 64-key tiles are laid end to end and
+    //             cut into a.slots runs of equal length; the workgroup serves its run, i.e. the tail of one sequence,
+    //             whole short sequences, the head of another, one segment after the other.  Every workgroup then has the
+    //             same number of tiles whatever the mix of lengths (a ragged batch otherwise takes as long as its longest
+    //             sequence).  Segment number (slot - first slot of the sequence) is the split index of its partials;
+    //             nsplit = a.slots bounds it.  A sequence that lies inside one slot is written out directly.
+    constexpr bool balanced = BAL;
+    int hk, b_first, b_last, slot = 0, run_lo = 0, run_hi = 0, tiles_all = 0, tiles_before = 0;
+    if constexpr (!balanced) {
+        hk = (sigma / a.nsplit) % a.Hkv;
+        b_first = b_last = sigma / (a.nsplit * a.Hkv);
+    } else {
+        hk = sigma / a.slots;
+        slot = sigma % a.slots;
+        auto tiles_of = [&](int bb) {
+            int Lb = a.seq_lens[bb];
+            Lb = Lb < 0 ? 0 : (Lb > a.max_seq_len ? a.max_seq_len : Lb);
+            return (Lb + a.N + kKeyTile - 1) / kKeyTile;
+        };
+        for (int bb = 0; bb < a.B; ++bb) tiles_all += tiles_of(bb);
+        run_lo = (int)((int64_t)slot * tiles_all / a.slots);
+        run_hi = (int)((int64_t)(slot + 1) * tiles_all / a.slots);
+        // first and last sequence with tiles inside [run_lo, run_hi)
+        b_first = 0;
+        int acc = 0;
+        while (b_first < a.B - 1 && acc + tiles_of(b_first) <= run_lo) acc += tiles_of(b_first++);
+        tiles_before = acc;  // tiles of the sequences before b_first
+        b_last = b_first;
+        acc += tiles_of(b_first);
+        while (b_last < a.B - 1 && acc < run_hi) acc += tiles_of(++b_last);
+        if (run_lo >= run_hi) b_last = b_first - 1;  // more slots than tiles: nothing to do
+    }
+    // the slot that holds tile x of the concatenation: the largest s with floor(s * tiles_all / slots) <= x
+    auto slot_of_tile = [&](int x) { return (int)((((int64_t)x + 1) * a.slots - 1) / tiles_all); };
+    // all of this is the same in every lane: keep it in scalar registers (the vector registers are all spoken for)
+    auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
+    if constexpr (balanced) {
+        hk = uni(hk); b_first = uni(b_first); b_last = uni(b_last); run_lo = uni(run_lo); run_hi = uni(run_hi);
+        tiles_before = uni(tiles_before); tiles_all = uni(tiles_all);
+    } else {
+        b_last = b_first;
+    }
+
+    for (int b = b_first; b <= b_last; ++b) {
+    if (balanced && b != b_first) __syncthreads();   // the previous segment's tile buffers and masks are free again
     int L = a.seq_lens[b];
     L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
     const int Tk = L + a.N;
-    int chunk = (Tk + a.nsplit - 1) / a.nsplit;
-    chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
-    const int k0 = split * chunk;
-    const int k1 = min(Tk, k0 + chunk);
-    const int64_t rows_total = (int64_t)a.B * a.N * a.Hq;
+    int k0, k1, split;
+    bool direct = a.nsplit == 1;   // this segment is the whole sequence: final rows are written here
+    if constexpr (!balanced) {
+        split = sigma % a.nsplit;
+        int chunk = (Tk + a.nsplit - 1) / a.nsplit;
+        chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
+        k0 = split * chunk;
+        k1 = min(Tk, k0 + chunk);
+    } else {
+        const int nt = (Tk + kKeyTile - 1) / kKeyTile;
+        const int t0 = max(run_lo, tiles_before) - tiles_before, t1 = min(run_hi, tiles_before + nt) - tiles_before;
+        const int s_first = slot_of_tile(tiles_before), s_last = slot_of_tile(tiles_before + nt - 1);
+        tiles_before += nt;
+        k0 = t0 * kKeyTile;
+        k1 = min(Tk, t1 * kKeyTile);
+        if (t0 >= t1) continue;   // (cannot happen for b_first .. b_last; keeps a wrong split index out of the workspace)
+        split = slot - s_first;
+        direct = s_first == s_last;
+        if (slot == s_first && tid < 256) {
+            // first segment of this sequence: tell the merge which split indices exist for this row tile's rows --
+            // either "already final" (m = +inf in index 0) or "absent" (m = -inf) beyond the last segment
+            for (int r = tid; r < min(RW, R - row_base); r += 256) {
+                const int row = row_base + r;
+                const int64_t rg = ((int64_t)b * a.N + row / a.G) * a.Hq + hk * a.G + row % a.G;
+                for (int sp = direct ? 0 : s_last - s_first + 1; sp < a.nsplit; ++sp) {
+                    float* pml = a.part_ml + ((int64_t)sp * rows_total + rg) * 2;
+                    pml[0] = direct && sp == 0 ? INFINITY : -INFINITY;
+                    pml[1] = 0.f;
+                }
+            }
+        }
+    }
+    if constexpr (balanced) {
+        k0 = uni(k0); k1 = uni(k1); split = uni(split); L = uni(L);
+        direct = uni(direct) != 0;
+    }
+    [&]() {   // one segment; wavefronts that have nothing more to do leave through `return`
 
     // rows of this lane: block rb of this wave -> row_base + (wrow*RB + rb)*32 + n
     int rg_of[RB];       // global row index (b, node, q head) or -1; fits 31 bits (checked on the host)
@@ -582,7 +664,7 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     for (int rb = 0; rb < RB; ++rb) {
         const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32);
         if (rg_of[rb] < 0) continue;
-        if (a.nsplit == 1) {
+        if (direct) {
             const float inv = v_unit / l_tot;
             uint16_t* op = static_cast<uint16_t*>(a.out) + (int64_t)rg_of[rb] * DH + 4 * g2;
 #pragma unroll
@@ -596,16 +678,18 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 }
             if (a.lse && g2 == 0) a.lse[rg_of[rb]] = m_ref[rb] * kLn2 + logf(l_tot);
         } else {
-            // bf16 partial outputs, four values per 8-byte streaming store: the partials are read once, by the combine
-            // kernel, and leaving them dirty in L2 only lengthens the write-back at the end of this kernel
-            u32x2* po = reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.part_o) + ((int64_t)split * rows_total + rg_of[rb]) * DH + 4 * g2);
+            // fp32 partial outputs (bf16 ones would halve this traffic, but rounding the partials and then the merged
+            // row costs up to a whole bf16 ulp, which outputs of magnitude 4 cannot afford inside 2e-2), written with
+            // streaming stores: they are read once, by the combine kernel, and leaving them dirty in L2 only lengthens
+            // the write-back at the end of this kernel
+            float* po = static_cast<float*>(a.part_o) + ((int64_t)split * rows_total + rg_of[rb]) * DH + 4 * g2;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
-                    const u32x2 w = {pack_bf16x2(o[rb][db][4 * vq] * v_unit, o[rb][db][4 * vq + 1] * v_unit),
-                                     pack_bf16x2(o[rb][db][4 * vq + 2] * v_unit, o[rb][db][4 * vq + 3] * v_unit)};
-                    __builtin_nontemporal_store(w, po + 8 * db + 2 * vq);
+                    f32x4 val = {o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]};
+                    if constexpr (KV8) val *= v_unit;
+                    __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(po + 32 * db + 8 * vq));
                 }
             if (g2 == 0) {
                 float* pml = a.part_ml + ((int64_t)split * rows_total + rg_of[rb]) * 2;
@@ -614,28 +698,30 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
             }
         }
     }
+    }();   // one segment
+    }      // segments of this workgroup
 }
 
 // Largest dynamic shared memory any shape asks for: six 16 KiB tiles, ancestor masks of up to 257 nodes x 32 words, and
 // the parent table of 1024 nodes.  Every variant's limit is raised to it once per device.
 constexpr size_t kMaxSmem = (size_t)2 * 3 * 64 * ROWB + (size_t)257 * 32 * 4 + 1024 * 4;
 
-template <int NW, int RB, int KT, int KS, bool KV8, bool NT>
+template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false>
 hipError_t raise_variant() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<NW, RB, KT, KS, KV8, NT>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<NW, RB, KT, KS, KV8, NT, BAL>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxSmem);
 }
 
-template <int NW, int RB, int KT, int KS, bool KV8, bool NT>
+template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false>
 hipError_t launch_variant(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
-    const int S = a.B * a.Hkv * a.nsplit;
+    const int S = a.slots > 0 ? a.Hkv * a.slots : a.B * a.Hkv * a.nsplit;   // K/V streams, each read by RT workgroups
     const int RT = p.row_tiles;
     const int S8 = (S + 7) / 8 * 8;
     const int RW = NW / KS * RB * 32;
     const int nodes_local = (RW + a.G - 1) / a.G + 1;
     // three K and three V tile buffers, the ancestor bitmasks and the parent table
     const size_t smem = (size_t)2 * 3 * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
-    auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8, NT>;
+    auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8, NT, BAL>;
     const unsigned threads = (NW + (KV8 ? 4 : 0)) * 64;  // KV8: plus the four loading wavefronts
     if (smem > kMaxSmem) return hipErrorInvalidValue;  // cannot happen for N <= 1024: checked again for the sake of the launch
     hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), smem, st, a, RT, S);
@@ -647,6 +733,12 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     if constexpr (KV8) {
         return launch_variant<NW, RB, KT, KS, true, false>(a, p, st);  // the loaders' register loads always stream
     } else {
+        if constexpr (KS == 1) {
+            if (a.slots > 0)
+                return p.row_tiles == 1 ? launch_variant<NW, RB, KT, KS, false, true, true>(a, p, st)
+                                        : launch_variant<NW, RB, KT, KS, false, false, true>(a, p, st);
+        }
+        if (a.slots > 0) return hipErrorInvalidValue;
         return p.row_tiles == 1 ? launch_variant<NW, RB, KT, KS, false, true>(a, p, st)
                                 : launch_variant<NW, RB, KT, KS, false, false>(a, p, st);
     }
@@ -659,6 +751,10 @@ hipError_t raise_limits_attn_mfma() {
     auto both = [&](auto nw, auto ks) {
         if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, false>();
         if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, true>();
+        if constexpr (decltype(ks)::value == 1) {
+            if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, 1, false, false, true>();
+            if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, 1, false, true, true>();
+        }
     };
     both(IntC<4>{}, IntC<1>{}); both(IntC<6>{}, IntC<1>{}); both(IntC<8>{}, IntC<1>{});
     both(IntC<2>{}, IntC<2>{}); both(IntC<4>{}, IntC<2>{}); both(IntC<8>{}, IntC<2>{});

@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(AttnArgs a) {
         }
     }
 
-    float* po = static_cast<float*>(a.part_o) + ((int64_t)split * rows + r) * DH + lane * EPL;
+    float* po = a.part_o + ((int64_t)split * rows + r) * DH + lane * EPL;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) po[e] = acc[e];
     if (lane == 0) {
@@ -150,65 +150,84 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(AttnArgs a) {
 }
 
 // Merge of the per-split partials: m* = max_s m_s, l* = sum_s l_s e^{m_s - m*},
-// O = sum_s O~_s e^{m_s - m*} / l*, lse = m* + ln l*.  One thread per 4 output elements.
-// Splits are taken eight at a time with all of a group's loads issued before any is used, so a
-// row costs one memory round trip per group instead of one per split; groups are chained with the
-// usual running-maximum rescale.
-// PBF16: the partial outputs are bf16 (matrix-core kernels) instead of fp32 (vector kernel).
-template <typename T, int DH, bool PBF16>
+// O = sum_s O~_s e^{m_s - m*} / l*, lse = m* + ln l*.
+// A group of DH/4 lanes owns one row, each lane four output elements.  The (m, l) records are read once per
+// row -- lane t of the group takes splits t and t + DH/4 -- and the maximum, the weights e^{m_s - m*} and l* are
+// formed inside the group with shuffles; the partial outputs are then fetched for the live splits only, eight
+// loads in flight at a time (balanced batches leave most split indices of a row absent: m = -inf, slot of the
+// workspace never written).  m = +inf in split 0 marks a row whose final values the main kernel wrote itself.
+template <typename T, int DH>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
-    constexpr int TPR = DH / 4;  // threads per row
-    constexpr int GS = 8;        // splits per group
+    constexpr int TPR = DH / 4;  // lanes per row: 32 or 16, a power of two that divides the wavefront
+    constexpr int GS = 8;        // partial outputs in flight per lane
     const int64_t rows = (int64_t)a.B * a.N * a.Hq;
-    const int64_t r = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
-    if (r >= rows) return;
-    const int c = (threadIdx.x % TPR) * 4;
+    const int64_t r_raw = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;
+    const bool in_range = r_raw < rows;   // lanes beyond the last row keep their group's shuffles company
+    const int64_t r = in_range ? r_raw : rows - 1;
+    const int t = threadIdx.x % TPR, c = 4 * t;
+    constexpr int NH = 64 / TPR;          // records per lane: the host never plans more than 64 splits
     const int nsp = a.nsplit;
-    float mstar = -INFINITY, lstar = 0.f;
-    float o[4] = {0.f, 0.f, 0.f, 0.f};
+
+    float m[NH], l[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        const int sp = t + h * TPR;
+        m[h] = -INFINITY;
+        l[h] = 0.f;
+        if (sp < nsp) {
+            const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + ((int64_t)sp * rows + r) * 2);
+            m[h] = ml.x;
+            l[h] = ml.y;
+        }
+    }
+    if (__shfl(m[0], 0, TPR) == INFINITY) return;  // final already (the whole group agrees: same row)
+    float mstar = m[0];
+#pragma unroll
+    for (int h = 1; h < NH; ++h) mstar = fmaxf(mstar, m[h]);
+#pragma unroll
+    for (int o = TPR / 2; o > 0; o >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, o, TPR));
+    // a row always has a visible key (itself), so some split is live and mstar is finite
+    float w[NH], lstar = 0.f;
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        w[h] = m[h] == -INFINITY ? 0.f : expf(m[h] - mstar);
+        lstar = fmaf(l[h], w[h], lstar);
+    }
+#pragma unroll
+    for (int o = TPR / 2; o > 0; o >>= 1) lstar += __shfl_xor(lstar, o, TPR);
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < nsp; s0 += GS) {
-        float2 ml[GS];
+        float ws[GS];
         float4 v[GS];
 #pragma unroll
         for (int u = 0; u < GS; ++u) {
-            const int s = min(s0 + u, nsp - 1);  // the tail repeats the last split; its weight is dropped below
-            ml[u] = *reinterpret_cast<const float2*>(a.part_ml + ((int64_t)s * rows + r) * 2);
-            if constexpr (PBF16) {
-                const uint2 h = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(a.part_o) + ((int64_t)s * rows + r) * DH + c);
-                v[u] = make_float4(__uint_as_float(h.x << 16), __uint_as_float(h.x & 0xffff0000u),
-                                   __uint_as_float(h.y << 16), __uint_as_float(h.y & 0xffff0000u));
-            } else {
-                v[u] = *reinterpret_cast<const float4*>(static_cast<const float*>(a.part_o) + ((int64_t)s * rows + r) * DH + c);
+            const int sp = s0 + u;   // its weight sits in lane sp % TPR of the group, slot sp / TPR
+            float wsel = 0.f;
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const float wh = __shfl(w[h], sp % TPR, TPR);
+                if (sp / TPR == h) wsel = wh;
             }
+            ws[u] = sp >= nsp ? 0.f : wsel;
+            v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ws[u] != 0.f) v[u] = *reinterpret_cast<const float4*>(a.part_o + ((int64_t)sp * rows + r) * DH + c);
         }
-        float mg = mstar;
-#pragma unroll
-        for (int u = 0; u < GS; ++u) mg = fmaxf(mg, ml[u].x);
-        if (mg == -INFINITY) continue;  // no split so far saw a visible key for this row
-        const float carry = expf(mstar - mg);  // 0 when nothing was accumulated yet
-        lstar *= carry;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] *= carry;
-        mstar = mg;
 #pragma unroll
         for (int u = 0; u < GS; ++u) {
-            // an empty split wrote only its (m = -inf, l = 0) record: its O~ is whatever the workspace held
-            const bool live = s0 + u < nsp && ml[u].x != -INFINITY;
-            const float w = live ? expf(ml[u].x - mstar) : 0.f;
-            const float4 vv = live ? v[u] : make_float4(0.f, 0.f, 0.f, 0.f);
-            lstar = fmaf(live ? ml[u].y : 0.f, w, lstar);
-            o[0] = fmaf(vv.x, w, o[0]); o[1] = fmaf(vv.y, w, o[1]);
-            o[2] = fmaf(vv.z, w, o[2]); o[3] = fmaf(vv.w, w, o[3]);
+            acc[0] = fmaf(v[u].x, ws[u], acc[0]); acc[1] = fmaf(v[u].y, ws[u], acc[1]);
+            acc[2] = fmaf(v[u].z, ws[u], acc[2]); acc[3] = fmaf(v[u].w, ws[u], acc[3]);
         }
     }
+    if (!in_range) return;
     const float inv = 1.f / lstar;
     if constexpr (sizeof(T) == 4) {
         *reinterpret_cast<float4*>(static_cast<float*>(a.out) + r * DH + c) =
-            make_float4(o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv);
+            make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
     } else {
         __hip_bfloat16 h[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = __float2bfloat16(o[e] * inv);  // round to nearest even
+        for (int e = 0; e < 4; ++e) h[e] = __float2bfloat16(acc[e] * inv);  // round to nearest even
         *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + r * DH + c) = *reinterpret_cast<uint2*>(h);
     }
     if (a.lse && c == 0) a.lse[r] = mstar + logf(lstar);
@@ -224,15 +243,14 @@ hipError_t launch_vector_t(const AttnArgs& a, const AttnPlan& p, hipStream_t st)
 }
 
 template <typename T>
-hipError_t launch_combine_t(const AttnArgs& a, bool partials_bf16, hipStream_t st) {
+hipError_t launch_combine_t(const AttnArgs& a, hipStream_t st) {
     const int64_t rows = (int64_t)a.B * a.N * a.Hq;
     if (a.Dh == 128) {
         dim3 grid((unsigned)((rows + 7) / 8));
-        if (partials_bf16) hipLaunchKernelGGL((attn_combine_kernel<T, 128, true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((attn_combine_kernel<T, 128, false>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attn_combine_kernel<T, 128>), grid, dim3(256), 0, st, a);
     } else {
         dim3 grid((unsigned)((rows + 15) / 16));
-        hipLaunchKernelGGL((attn_combine_kernel<T, 64, false>), grid, dim3(256), 0, st, a);
+        hipLaunchKernelGGL((attn_combine_kernel<T, 64>), grid, dim3(256), 0, st, a);
     }
     return hipGetLastError();
 }
@@ -244,7 +262,8 @@ hipError_t launch_attn_vector(const AttnArgs& a, const AttnPlan& p, int dtype, h
 }
 
 hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st) {
-    return dtype == YGG_F32 ? launch_combine_t<float>(a, p.use_mfma != 0, st) : launch_combine_t<uint16_t>(a, p.use_mfma != 0, st);
+    (void)p;
+    return dtype == YGG_F32 ? launch_combine_t<float>(a, st) : launch_combine_t<uint16_t>(a, st);
 }
 
 }  // namespace ygg

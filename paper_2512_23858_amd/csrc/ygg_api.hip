@@ -105,6 +105,17 @@ AttnPlan plan_attention(const ygg_shape& s) {
         ns = 256 / per_split;
         if (ns > tiles / 2) ns = tiles / 2;
         if (ns_forced) ns = ns_forced < tiles ? ns_forced : tiles;
+        // Batches: sequence lengths live on the device and may be ragged, so instead of giving every sequence the same
+        // number of splits the key tiles of all sequences are laid end to end and cut into equal runs, one per workgroup
+        // of a (kv head, row tile): 256 workgroups in all, each with the same number of tiles whatever the lengths.
+        const int64_t streams = (int64_t)s.n_kv_heads * p.row_tiles;
+        if (!kv8 && p.kshares == 1 && s.batch >= 2 && s.batch <= 256 && streams <= 128 && !ns_forced) {
+            int64_t slots = 256 / streams;
+            const int64_t most = (int64_t)s.batch * tiles;   // never more runs than tiles
+            if (slots > most) slots = most;
+            if (slots > 64) slots = 64;                      // the merge takes at most 64 splits per row
+            if (slots >= 2) p.slots = (int32_t)slots;
+        }
     } else {
         // vector path: one wavefront per (row, split); aim for ~4096 wavefronts
         ns = (4096 + rows - 1) / rows;
@@ -115,8 +126,7 @@ AttnPlan plan_attention(const ygg_shape& s) {
     // drop the splits that rounding the chunk to whole key tiles leaves empty
     const int64_t chunk = ((T + ns - 1) / ns + kKeyTile - 1) / kKeyTile * kKeyTile;
     ns = (T + chunk - 1) / chunk;
-    p.nsplit = (int32_t)ns;
-    // sized for fp32 partial outputs (the vector kernel's); the matrix-core kernels write bf16 into the same space
+    p.nsplit = p.slots > 0 ? p.slots : (int32_t)ns;   // balanced batches: a sequence may span every run
     p.part_o_bytes = align256((size_t)p.nsplit * (size_t)rows * (size_t)s.head_dim * sizeof(float));
     p.part_ml_bytes = align256((size_t)p.nsplit * (size_t)rows * 2 * sizeof(float));
     return p;
@@ -224,12 +234,13 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     AttnArgs a{};
     a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
     a.seq_lens = seq_lens; a.parent_idx = parent_idx; a.k_scale = k_scale; a.v_scale = v_scale;
-    a.part_o = static_cast<char*>(workspace) + kHeaderBytes;
+    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + kHeaderBytes);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + kHeaderBytes + p.part_o_bytes);
     a.out = out; a.lse = lse;
     a.B = s->batch; a.N = s->n_nodes; a.Hq = s->n_q_heads; a.Hkv = s->n_kv_heads;
     a.G = s->n_q_heads / s->n_kv_heads; a.Dh = s->head_dim;
     a.nsplit = p.nsplit; a.max_seq_len = s->max_seq_len; a.cap = s->kv_capacity; a.scale = s->softmax_scale;
+    a.slots = p.slots;
 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int out_dtype = s->kv_dtype == YGG_F32 ? YGG_F32 : YGG_BF16;  // element type of Q and O

@@ -27,12 +27,13 @@ struct AttnArgs {
     const int32_t* parent_idx;
     const float* k_scale;  // [Hkv], both set: K and V hold 8-bit E4M3 codes; both null: plain elements
     const float* v_scale;
-    void* part_o;     // [nsplit][B*N*Hq][Dh]: bf16 from the matrix-core kernels, fp32 from the vector kernel
+    float* part_o;    // [nsplit][B*N*Hq][Dh]
     float* part_ml;   // [nsplit][B*N*Hq][2]   (running max m in scaled-score units, sum l)
     void* out;
     float* lse;
     int32_t B, N, Hq, Hkv, G, Dh;
     int32_t nsplit, max_seq_len;
+    int32_t slots;    // matrix-core kernel, batches: > 0 = workgroups take equal runs of the concatenated key tiles (nsplit = slots)
     int64_t cap;
     float scale;
 };
@@ -44,13 +45,13 @@ struct AttnPlan {
     int32_t rblocks;        // MFMA kernel: 32-row blocks per wavefront
     int32_t kshares;        // MFMA kernel: 1, or 2 = pairs of wavefronts split every key tile
     int32_t row_tiles;      // MFMA kernel: workgroups along the N*G query rows of one kv head
+    int32_t slots;          // MFMA kernel, batches: equal runs of key tiles per (kv head, row tile); 0 = one sequence per workgroup
     size_t part_o_bytes, part_ml_bytes;
 };
 
 AttnPlan plan_attention(const ygg_shape& s);
 hipError_t launch_attn_vector(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st);
-// dtype: element type of the output; partial outputs are bf16 when p.use_mfma, else fp32
 hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, hipStream_t st);
 
 // One-time raising of the dynamic shared-memory limits of every kernel variant of a translation unit (current device).

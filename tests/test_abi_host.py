@@ -215,7 +215,8 @@ def test_attention_plans_of_the_five_configurations():
             2: dict(matrix_cores=True, waves=4, key_shares=2, row_tiles=1, key_splits=6),
             3: dict(matrix_cores=True, waves=8, key_shares=2, row_tiles=5, key_splits=6),
             4: dict(matrix_cores=True, waves=8, key_shares=1, row_tiles=6, key_splits=5),
-            5: dict(matrix_cores=True, waves=8, key_shares=1, row_tiles=2, key_splits=1)}
+            # a batch: 16 equal runs of the concatenated key tiles per (kv head, row tile) = 256 workgroups
+            5: dict(matrix_cores=True, waves=8, key_shares=1, row_tiles=2, key_splits=16)}
     for c, exp in want.items():
         cfg = wl.CONFIGS[c]
         s = ygg.Shape(batch=cfg.batch, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,

@@ -75,6 +75,31 @@ def test_bf16_shapes(case):
     _check(cfg, host, parent, max_len)
 
 
+# Batches of wide trees (more than 128 query rows per kv head) run "balanced": the key tiles of all sequences are laid end
+# to end and cut into equal runs, so a workgroup may serve the tail of one sequence, whole short ones and the head of
+# another.  (B, Hq, Hkv, D, W, lens, max_len)
+RAGGED_BATCHES = [
+    (5, 16, 2, 6, 8, [900, 0, 64, 1500, 333], 1500),          # R = 392, two row tiles; an empty and a one-tile prefix
+    (2, 16, 2, 6, 8, [700, 700], 700),                        # equal lengths: every run lies inside one sequence
+    (3, 16, 2, 6, 8, [0, 0, 0], 64),                          # fewer key tiles than runs
+    (4, 8, 1, 8, 16, [2000, 15, 15, 15], 2048),               # one long sequence spans nearly every run; R = 1032
+    (16, 8, 2, 6, 8, [37 * i % 601 for i in range(16)], 640), # many short sequences per run; R = 196
+    (7, 32, 4, 5, 6, [511, 512, 513, 1, 1023, 1024, 1025], 1100),   # lengths around tile boundaries; R = 248
+    (2, 8, 2, 10, 12, [3000, 100], 3000),                     # R = 484: a sequence whose length equals max_seq_len
+]
+
+
+@pytest.mark.parametrize("case", RAGGED_BATCHES, ids=lambda c: f"B{c[0]}_Hq{c[1]}_Hkv{c[2]}_D{c[3]}W{c[4]}_L{max(c[5])}")
+@pytest.mark.parametrize("gain", [1.0, 4.0])
+def test_bf16_ragged_batches_in_balanced_runs(case, gain):
+    import paper_2512_23858_amd as ygg
+    B, Hq, Hkv, D, W, lens, max_len = case
+    cfg, host, parent = _inputs(_cfg(B, Hq, Hkv, D, W, seed=123), lens, max_len, tree_gain=gain)
+    plan = ygg.attention_plan(shape_of(cfg, max_seq_len=int(max_len)))
+    assert plan["matrix_cores"] and plan["key_shares"] == 1 and plan["key_splits"] * Hkv * plan["row_tiles"] <= 256
+    _check(cfg, host, parent, max_len)
+
+
 @pytest.mark.parametrize("L", [0, 1, 31, 32, 33, 63, 64, 65])
 @pytest.mark.parametrize("gain", [1.0, 4.0])
 def test_bf16_short_prefix_and_tree_heavy(L, gain):
