@@ -161,11 +161,11 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     int k0, k1, split;
     bool direct = a.nsplit == 1;   // this segment is the whole sequence: final rows are written here
     if constexpr (!balanced) {
+        // the sequence's own 64-key tiles, dealt out as evenly as whole tiles allow (splits differ by at most one tile)
         split = sigma % a.nsplit;
-        int chunk = (Tk + a.nsplit - 1) / a.nsplit;
-        chunk = (chunk + kKeyTile - 1) / kKeyTile * kKeyTile;
-        k0 = split * chunk;
-        k1 = min(Tk, k0 + chunk);
+        const int nt = (Tk + kKeyTile - 1) / kKeyTile;
+        k0 = (int)((int64_t)split * nt / a.nsplit) * kKeyTile;
+        k1 = min(Tk, (int)((int64_t)(split + 1) * nt / a.nsplit) * kKeyTile);
     } else {
         const int nt = (Tk + kKeyTile - 1) / kKeyTile;
         const int t0 = max(run_lo, tiles_before) - tiles_before, t1 = min(run_hi, tiles_before + nt) - tiles_before;

@@ -100,10 +100,11 @@ AttnPlan plan_attention(const ygg_shape& s) {
         p.row_tiles = (R + rw - 1) / rw;
         // fill the 256 CUs once -- the tile buffers leave room for one workgroup per CU, and a second round of
         // workgroups pays the start-up latency again while more splits add partial-result traffic --
-        // with at least two key tiles per split
+        // with about three key tiles per split at least (config 2's 17 tiles: 5 / 6 / 8 splits measured 16.4 / 15.7 / 16.4 us
+        // per layer)
         const int64_t per_split = (int64_t)s.batch * s.n_kv_heads * p.row_tiles;
         ns = 256 / per_split;
-        if (ns > tiles / 2) ns = tiles / 2;
+        if (ns > (tiles + 2) / 3) ns = (tiles + 2) / 3;
         if (ns_forced) ns = ns_forced < tiles ? ns_forced : tiles;
         // Batches: sequence lengths live on the device and may be ragged, so instead of giving every sequence the same
         // number of splits the key tiles of all sequences are laid end to end and cut into equal runs, one per workgroup
@@ -123,9 +124,12 @@ AttnPlan plan_attention(const ygg_shape& s) {
     }
     if (ns < 1) ns = 1;
     if (ns > 64) ns = 64;
-    // drop the splits that rounding the chunk to whole key tiles leaves empty
-    const int64_t chunk = ((T + ns - 1) / ns + kKeyTile - 1) / kKeyTile * kKeyTile;
-    ns = (T + chunk - 1) / chunk;
+    if (!p.use_mfma) {
+        // vector kernel: equal chunks rounded up to whole key tiles; drop the splits that rounding leaves empty
+        // (the matrix-core kernel deals whole tiles out evenly instead, and no split of at most `tiles` is empty)
+        const int64_t chunk = ((T + ns - 1) / ns + kKeyTile - 1) / kKeyTile * kKeyTile;
+        ns = (T + chunk - 1) / chunk;
+    }
     p.nsplit = p.slots > 0 ? p.slots : (int32_t)ns;   // balanced batches: a sequence may span every run
     p.part_o_bytes = align256((size_t)p.nsplit * (size_t)rows * (size_t)s.head_dim * sizeof(float));
     p.part_ml_bytes = align256((size_t)p.nsplit * (size_t)rows * 2 * sizeof(float));

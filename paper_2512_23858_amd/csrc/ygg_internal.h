@@ -15,8 +15,10 @@ constexpr int kHeaderCounters = YGG_WORKSPACE_HEADER_BYTES / 4;
 
 // ---- tree attention ---------------------------------------------------------------------------
 // Key index space of sequence b: [0, L_b) are cache rows, [L_b, L_b + N) are the tree's own rows.
-// Split s of nsplit covers [s*chunk, min((s+1)*chunk, L_b+N)), chunk = ceil((L_b+N)/nsplit)
-// rounded up to kKeyTile.  Every split writes an un-normalised partial (m, l, O~) per query row.
+// Vector kernel: split s of nsplit covers [s*chunk, min((s+1)*chunk, L_b+N)), chunk = ceil((L_b+N)/nsplit)
+// rounded up to kKeyTile.  Matrix-core kernel: split s covers the 64-key tiles floor(s*nt/nsplit) ..
+// floor((s+1)*nt/nsplit) - 1 of the sequence's nt tiles.  Every split writes an un-normalised partial
+// (m, l, O~) per query row.
 struct AttnArgs {
     const void* q;
     const void* k_cache;
