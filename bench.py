@@ -37,7 +37,7 @@ DEFAULT_LAYERS = {1: 1, 2: 32, 3: 32, 4: 8, 5: 4}
 # (a benchmark run cannot collect counters itself) by the commands in TRAFFIC_SOURCE, for the kernel as it stands in
 # the commit that file names.  Reported only together with that source.
 TRAFFIC_SOURCE = "profiles/attn_mfma_hbm_traffic.md"
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {2: 26_434_253, 3: 38_260_019, 4: 178_742_272, 5: 406_039_142}
 
 
 def attention_work(cfg, lens, kv_bytes=None):
