@@ -17,13 +17,8 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller; the ygg_shape struct is HOST
  *     memory and is only read during the call.  The library never allocates, frees or keeps
  *     device memory; scratch space is the caller's `workspace` (size from ygg_workspace_bytes,
- *     256-byte aligned).  Its first YGG_WORKSPACE_HEADER_BYTES hold arrival counters through which
- *     the workgroups of one launch find out who finishes a job last (nothing ever waits on them):
- *     they must be zero when a call is enqueued and every call leaves them zero again, so a
- *     workspace is zero-filled once after allocation (ygg_workspace_init, or any memset of the
- *     header) and can then serve any sequence of calls, operations and shapes on one stream.  The
- *     rest of the workspace is scratch: contents undefined on entry and on return.  Calls that
- *     may run concurrently need workspaces of their own.
+ *     256-byte aligned, contents undefined on entry and on return).  Calls that may run
+ *     concurrently need workspaces of their own.
  *   - Calls only enqueue kernels on `hip_stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and never synchronise, so a sequence of calls can be captured in a HIP
  *     graph.  All shapes are static: nothing on the host depends on device data.  This is the
@@ -87,18 +82,8 @@ typedef struct {
     int32_t max_seq_len;   /* host-known upper bound of seq_lens[b] (sizes the launch grids) */
 } ygg_shape;
 
-/* Bytes at the start of every workspace that must be zero between calls (see the conventions above). */
-#define YGG_WORKSPACE_HEADER_BYTES 65536
-
-/* Bytes of workspace the given operation needs for this shape, header included (0 if the shape is invalid). */
+/* Bytes of workspace the given operation needs for this shape (0 if the shape is invalid). */
 size_t ygg_workspace_bytes(const ygg_shape *shape, int32_t op /* ygg_op */, int32_t n_layers);
-
-/*
- * Zero-fills the header of a freshly allocated workspace with a small fill kernel on hip_stream (call
- * it once per allocation; a zero-initialised allocation needs no call).  workspace_bytes must be at
- * least YGG_WORKSPACE_HEADER_BYTES.
- */
-int32_t ygg_workspace_init(void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char *ygg_status_string(int32_t status);
@@ -175,7 +160,7 @@ int32_t ygg_tree_attention_fp8kv(const ygg_shape *shape,
  *   draft_logits [B,F,V] fp32    row p belongs to node 1+(d-2)W+p (node 0 for d = 1)
  *   parent_idx, token_ids [B,N] int32 and cum_logprob [B,N] fp32: in/out; depth d-1 entries are
  *   read, depth d entries written.  The caller initialises node 0 (parent -1, cum 0).
- * Requires N == 1 + D*W, F*V >= W and B <= 16384 (one header counter per sequence).
+ * Requires N == 1 + D*W and F*V >= W.
  */
 int32_t ygg_equal_growth_expand(const ygg_shape *shape, int32_t d, const float *draft_logits,
                                 int32_t *parent_idx, int32_t *token_ids, float *cum_logprob,
@@ -214,7 +199,7 @@ int32_t ygg_equal_growth_expand_static(const ygg_shape *shape, int32_t d, const 
  *                int32 node; int32 token}, the first `count` valid and ordered best first.  After
  *                step t it holds the best W*(D-t) untaken offers: an entry of rank r cannot be
  *                taken before r/W more steps, so nothing else can ever become a node.
- * Requires N == 1 + D*W, V >= W, N*V < 2^32, W*F + W*(D-t+1) <= 4096 and B*(F+1) <= 16384.
+ * Requires N == 1 + D*W, V >= W, N*V < 2^32 and W*F + W*(D-t+1) <= 4096.
  */
 size_t ygg_attach_pool_bytes(const ygg_shape *shape);
 int32_t ygg_equal_growth_attach(const ygg_shape *shape, int32_t t, const float *draft_logits,
@@ -272,7 +257,6 @@ int32_t ygg_prune_for_verification(const ygg_shape *shape, int32_t w_verify,
  *   k_cache, v_cache [n_layers,B,cap,Hkv,Dh]  kv_dtype, updated in place
  *                    (with YGG_FP8_E4M3 the four K/V arrays hold one-byte codes; rows are copied as bytes)
  *   seq_lens [B] int32 in/out; accept_len [B], accept_path [B,D+1], bonus_token [B] int32 out
- * Requires B <= 16384 (one header counter per sequence).
  */
 int32_t ygg_accept_and_compact(const ygg_shape *shape, int32_t n_layers,
                                const float *target_logits, const int32_t *target_tokens,

@@ -23,8 +23,6 @@ from .binding import (  # noqa: F401
     tree_attention,
     tree_attention_fp8kv,
     workspace_bytes,
-    workspace_init,
-    WORKSPACE_HEADER_BYTES,
     OP_ATTENTION,
     OP_EXPAND,
     OP_ACCEPT,

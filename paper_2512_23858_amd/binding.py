@@ -14,7 +14,6 @@ import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 OP_ATTENTION, OP_EXPAND, OP_ACCEPT, OP_ATTACH = 0, 1, 2, 3
-WORKSPACE_HEADER_BYTES = 65536
 F32, BF16, FP8_E4M3 = 0, 1, 2
 
 
@@ -89,8 +88,6 @@ def load_library() -> ctypes.CDLL:
         lib.ygg_debug_validate.argtypes = [shp] + [vp] * 4 + [i32, vp, vp]
         lib.ygg_accept_and_compact.restype = i32
         lib.ygg_accept_and_compact.argtypes = [shp, i32] + [vp] * 12 + [vp, sz, vp]
-        lib.ygg_workspace_init.restype = i32
-        lib.ygg_workspace_init.argtypes = [vp, sz, vp]
         lib.ygg_init.restype = i32
         lib.ygg_init.argtypes = []
         lib.ygg_debug_set_attention_plan.restype = i32
@@ -112,19 +109,12 @@ def workspace_bytes(shape: Shape, op: int, n_layers: int = 0) -> int:
     return int(load_library().ygg_workspace_bytes(ctypes.byref(cs), op, n_layers))
 
 
-def workspace_init(workspace):
-    """ygg_workspace_init: zero-fills the header of a freshly allocated workspace (once per allocation)."""
-    wsp, wsn = _ws(workspace)
-    _check(load_library().ygg_workspace_init(wsp, wsn, _stream()), "ygg_workspace_init")
-    return workspace
-
-
 def new_workspace(shape: Shape, op: int, n_layers: int = 0, device="cuda:0"):
-    """Allocates a workspace for (shape, op) through torch and prepares its header."""
+    """Allocates a workspace for (shape, op) through torch (contents undefined, as the library expects)."""
     n = workspace_bytes(shape, op, n_layers)
     if n == 0:
         raise ValueError("invalid shape for a workspace")
-    return workspace_init(torch.empty(n, dtype=torch.uint8, device=device))
+    return torch.empty(n, dtype=torch.uint8, device=device)
 
 
 def _dev(t, dtype=None, name="tensor"):

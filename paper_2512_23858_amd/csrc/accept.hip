@@ -2,23 +2,20 @@
 // speculation management" stage that idles the GPU when it runs on the host; Sec. 4.1 under
 // Eq. 2: bonus token; Sec. 6: the TokenTree's K/V bookkeeping).
 //
-// Two kernels:
-//   argmax_match    grid (tree node, vocab chunk): coalesced 16-byte streaming of the verifier's
-//                   fp32 logits, first maximum per chunk.  The workgroup that finishes a sequence's
-//                   last chunk (a counter in the workspace header tells it so; nobody waits) goes on
-//                   with that sequence's path match: it finishes the argmax, marks every node whose
-//                   whole root path matches, picks the deepest (lowest index on ties), writes the
-//                   path, the accepted length and the bonus token, and advances seq_lens.
-//                   (With the argmax given by the caller the match runs alone, one workgroup per sequence.)
+// Three kernels:
+//   argmax_partial  grid (tree node, vocab chunk): coalesced 16-byte streaming of the verifier's
+//                   fp32 logits, first maximum per chunk.
+//   path_match      one workgroup per sequence: finishes the argmax, marks every node whose whole
+//                   root path matches, picks the deepest (lowest index on ties), writes the path,
+//                   the accepted length and the bonus token, and advances seq_lens.
 //   compact         grid (path slot, sequence, layer): copies the accepted nodes' K and V rows
 //                   behind the old end of the cache.
 #include "ygg_internal.h"
-#include "ygg_device.h"
 
 namespace ygg {
 namespace {
 
-struct __align__(8) ArgPart {
+struct ArgPart {
     float val;
     int32_t idx;
 };
@@ -27,10 +24,7 @@ __device__ __forceinline__ void take_first_max(float& v, int& i, float v2, int i
     if (v2 > v || (v2 == v && i2 < i)) { v = v2; i = i2; }
 }
 
-__device__ __forceinline__ void match_sequence(const AcceptArgs& a, int b);
-
-__global__ __launch_bounds__(256) void argmax_match_kernel(AcceptArgs a) {
-    __shared__ uint32_t last_flag;
+__global__ __launch_bounds__(256) void argmax_partial_kernel(AcceptArgs a) {
     __shared__ float sv[4];
     __shared__ int si[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -69,20 +63,17 @@ __global__ __launch_bounds__(256) void argmax_match_kernel(AcceptArgs a) {
         ArgPart p;
         p.val = bv;
         p.idx = bi;
-        store_coherent(static_cast<ArgPart*>(a.part) + (row * a.nchunk + c), p);
+        static_cast<ArgPart*>(a.part)[row * a.nchunk + c] = p;
     }
-    const int b = (int)(row / a.N);
-    if (!arrive_and_check_last(a.counters + b, (uint32_t)(a.N * a.nchunk), &last_flag)) return;
-    match_sequence(a, b);
 }
 
-// One workgroup of 256 threads; the chunk maxima (if any) were written by coherent stores.
-__device__ __forceinline__ void match_sequence(const AcceptArgs& a, const int b) {
+__global__ __launch_bounds__(256) void path_match_kernel(AcceptArgs a) {
     __shared__ int parent_s[kMaxNodes];
     __shared__ int tstar_s[kMaxNodes];
     __shared__ int token_s[kMaxNodes];
     __shared__ unsigned long long best_s[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x;
     const int N = a.N;
 
     for (int i = tid; i < N; i += 256) {
@@ -101,7 +92,7 @@ __device__ __forceinline__ void match_sequence(const AcceptArgs& a, const int b)
             for (int c0 = 0; c0 < a.nchunk; c0 += 8) {
                 ArgPart pc[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) pc[u] = load_coherent(pp + min(c0 + u, a.nchunk - 1));
+                for (int u = 0; u < 8; ++u) pc[u] = pp[min(c0 + u, a.nchunk - 1)];
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
                     if (c0 + u < a.nchunk && (t == 0x7fffffff || pc[u].val > bv || (pc[u].val == bv && pc[u].idx < t))) {
@@ -155,8 +146,6 @@ __device__ __forceinline__ void match_sequence(const AcceptArgs& a, const int b)
     }
 }
 
-__global__ __launch_bounds__(256) void path_match_kernel(AcceptArgs a) { match_sequence(a, (int)blockIdx.x); }
-
 __global__ __launch_bounds__(256) void compact_kernel(AcceptArgs a) {
     const int k = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
     if (k >= a.accept_len[b]) return;
@@ -194,8 +183,11 @@ AcceptPlan plan_accept(const ygg_shape& s) {
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
     hipError_t e;
-    if (a.target_logits) hipLaunchKernelGGL(argmax_match_kernel, dim3((unsigned)(a.B * a.N), (unsigned)a.nchunk), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(path_match_kernel, dim3((unsigned)a.B), dim3(256), 0, st, a);
+    if (a.target_logits) {
+        hipLaunchKernelGGL(argmax_partial_kernel, dim3((unsigned)(a.B * a.N), (unsigned)a.nchunk), dim3(256), 0, st, a);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(path_match_kernel, dim3((unsigned)a.B), dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (a.n_layers > 0) {
         hipLaunchKernelGGL(compact_kernel, dim3((unsigned)(a.D + 1), (unsigned)a.B, (unsigned)a.n_layers), dim3(256), 0, st, a);

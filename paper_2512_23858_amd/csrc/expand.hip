@@ -2,16 +2,16 @@
 // node p, token v) with the largest cumulative draft log-probability (paper Sec. 4.2, "Draft
 // Width Selection").
 //
-// One launch, two phases:
-//   scan    every workgroup of the grid (frontier row, vocab chunk of 4096) streams its fp32 logits
-//           once, coalesced, and leaves per chunk {max, sum exp(x - max) in fp64, the chunk's W
-//           largest logits, best first}.  Inside one row the candidate order is the order of the raw
-//           logits, so the chunk lists are exact whatever the row's normaliser turns out to be.
-//   merge   the workgroup that finishes a sequence's last chunk (a counter in the workspace header
-//           tells it so; nobody waits) computes per-row log-sum-exp from the chunk statistics, the
-//           fp64 score cum[p] + (x - lse_p) of every list head, the W lists with the best heads (no
-//           entry of any other list can be among the W best), and finally the W best of those lists'
-//           W*W entries; ties go to the lower flat index p*V + v.
+// Two kernels:
+//   expand_scan   grid (frontier row, vocab chunk of 4096): streams the fp32 logits once,
+//                 coalesced, and leaves per chunk {max, sum exp(x - max) in fp64, the chunk's W
+//                 largest logits, best first}.  Inside one row the candidate order is the order
+//                 of the raw logits, so the chunk lists are exact whatever the row's normaliser
+//                 turns out to be.
+//   expand_merge  one workgroup per sequence: per-row log-sum-exp from the chunk statistics, the
+//                 fp64 score cum[p] + (x - lse_p) of every list head, the W lists with the best
+//                 heads (no entry of any other list can be among the W best), and finally the W
+//                 best of those lists' W*W entries; ties go to the lower flat index p*V + v.
 //
 // Selection of "the W best of a workgroup's candidates" (used three times) never sorts and has no
 // serial per-element rounds on its main path: each wavefront bisects, with ballots, for the W-th
@@ -34,7 +34,7 @@ struct ChunkStat {
     float maxv;
     int32_t count;
 };
-struct __align__(8) Cand {
+struct Cand {
     float val;
     int32_t idx;
 };
@@ -171,10 +171,10 @@ __device__ __forceinline__ int merged_rank(const TopWShared& sh, int wave, int l
 }
 
 // ---- scan ---------------------------------------------------------------------------------------
-// Scan of one (row, chunk); the chunk's statistics and list go to the workspace by coherent stores.
-__device__ __forceinline__ void scan_chunk(const ExpandArgs& a, TopWShared& sh) {
+__global__ __launch_bounds__(kScanThreads) void expand_scan_kernel(ExpandArgs a) {
     __shared__ double red_d[4];
     __shared__ float red_f[4];
+    __shared__ TopWShared sh;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -224,7 +224,7 @@ __device__ __forceinline__ void scan_chunk(const ExpandArgs& a, TopWShared& sh) 
         st.sumexp = (red_d[0] + red_d[1]) + (red_d[2] + red_d[3]);
         st.maxv = cmax;
         st.count = min(a.W, c1 - c0);
-        store_coherent(static_cast<ChunkStat*>(a.stats) + (row * a.nchunk + c), st);
+        static_cast<ChunkStat*>(a.stats)[row * a.nchunk + c] = st;
     }
     Entry mine;
     const int rank = merged_rank(sh, wave, lane, mine);
@@ -232,7 +232,7 @@ __device__ __forceinline__ void scan_chunk(const ExpandArgs& a, TopWShared& sh) 
         Cand cd;
         cd.val = float_of((uint32_t)(mine.key >> 32));
         cd.idx = (int32_t)mine.tie;
-        store_coherent(static_cast<Cand*>(a.cands) + ((row * a.nchunk + c) * a.W + rank), cd);
+        static_cast<Cand*>(a.cands)[(row * a.nchunk + c) * a.W + rank] = cd;
     }
 }
 
@@ -240,17 +240,20 @@ __device__ __forceinline__ void scan_chunk(const ExpandArgs& a, TopWShared& sh) 
 constexpr size_t merge_scratch_bytes(int lpt) { return (size_t)256 * lpt * 12; }
 
 template <int LPT>  // chunk lists per thread
-__device__ __forceinline__ void merge_sequence(const ExpandArgs& a, const int b, unsigned char* raw, TopWShared& sh) {
+__global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
     constexpr int KMAX = 256 * LPT;
-    // scratch for the chunk statistics: merge_scratch_bytes(LPT) of dynamic LDS
+    // scratch for the chunk statistics
+    extern __shared__ __align__(16) unsigned char raw[];  // merge_scratch_bytes(LPT)
     double* ssum = reinterpret_cast<double*>(raw);               // [KMAX]
     float* smax = reinterpret_cast<float*>(raw + KMAX * 8);      // [KMAX]
+    __shared__ TopWShared sh;
     __shared__ double lse_s[kMaxWidth];
     __shared__ double cum_s[kMaxWidth];
     __shared__ uint32_t sel[kMaxWidth];       // the lists with the W best heads
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int b = blockIdx.x;
     const int base_prev = a.d == 1 ? 0 : 1 + (a.d - 2) * a.W;
     const int base_new = 1 + (a.d - 1) * a.W;
     const int K = a.F * a.nchunk;  // number of chunk lists, list q = p*nchunk + c
@@ -273,8 +276,8 @@ __device__ __forceinline__ void merge_sequence(const ExpandArgs& a, const int b,
         head[u].idx = 0;
         if (q < K) {
             // a chunk is never empty, so its list has a head: both loads go out together
-            const ChunkStat st = load_coherent(stats + q);
-            head[u] = load_coherent(cands + (int64_t)q * a.W);
+            const ChunkStat st = stats[q];
+            head[u] = cands[(int64_t)q * a.W];
             smax[q] = st.maxv;
             ssum[q] = st.sumexp;
             cnt[u] = list_len(q);
@@ -333,7 +336,7 @@ __device__ __forceinline__ void merge_sequence(const ExpandArgs& a, const int b,
         Entry r = {0, kNone, 0};
         if (slot < nsel * a.W) {
             const int pos = slot / nsel, s = slot % nsel;
-            if (pos < sel_cnt[s]) r = entry_of(sel[s], load_coherent(cands + ((int64_t)sel[s] * a.W + pos)));
+            if (pos < sel_cnt[s]) r = entry_of(sel[s], cands[(int64_t)sel[s] * a.W + pos]);
         }
         return r;
     };
@@ -354,27 +357,14 @@ __device__ __forceinline__ void merge_sequence(const ExpandArgs& a, const int b,
     }
 }
 
-// grid (B*F rows, nchunk); the workgroup that completes sequence b's F*nchunk chunks merges them
-template <int LPT>
-__global__ __launch_bounds__(kScanThreads) void expand_kernel(ExpandArgs a) {
-    extern __shared__ __align__(16) unsigned char raw[];
-    __shared__ TopWShared sh;
-    __shared__ uint32_t last_flag;
-    scan_chunk(a, sh);
-    const int b = (int)(blockIdx.x / (unsigned)a.F);
-    if (!arrive_and_check_last(a.counters + b, (uint32_t)(a.F * a.nchunk), &last_flag)) return;
-    merge_sequence<LPT>(a, b, raw, sh);
-}
-
 // ---- equal growth with free attachment -----------------------------------------------------------
 // Every node, once the drafter has run on it, offers its W most probable tokens; the pool holds the
 // offers not yet taken; a step takes the W best of the pool (paper Sec. 4.2: the W new leaves of a
-// step may hang anywhere in the partial tree).  Two kernels per step: attach_rows scans the new rows
-// (per-chunk statistics and top-W lists, as above) and turns them into each row's W offers,
-// attach_pool sorts pool + offers, emits the W new nodes and keeps the best W*(D-t) of the
+// step may hang anywhere in the partial tree).  Three kernels per step: expand_scan (above) leaves
+// per-chunk statistics and top-W lists of the new rows, attach_rows turns them into each row's W
+// offers, attach_pool sorts pool + offers, emits the W new nodes and keeps the best W*(D-t) of the
 // rest: an entry of rank r needs r / W more steps before it can be taken and later offers only push
-// it down, so nothing beyond the slots still to be filled can ever be chosen.  Scan and offers share
-// one launch: the workgroup that finishes a row's last chunk turns the row's lists into its offers.
+// it down, so nothing beyond the slots still to be filled can ever be chosen.
 struct __align__(16) Offer {
     double score;
     int32_t node;
@@ -386,10 +376,6 @@ template <int EPT>  // list entries per thread: nchunk * W <= 256 * EPT
 __global__ __launch_bounds__(256) void attach_rows_kernel(ExpandArgs a) {
     __shared__ TopWShared sh;
     __shared__ double lse_sh;
-    __shared__ uint32_t last_flag;
-    scan_chunk(a, sh);
-    // counters [0, B) belong to the sequences (unused here), [B, B + B*F) to the rows
-    if (!arrive_and_check_last(a.counters + a.B + blockIdx.x, (uint32_t)a.nchunk, &last_flag)) return;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t row = blockIdx.x;  // b*F + p
@@ -408,7 +394,7 @@ __global__ __launch_bounds__(256) void attach_rows_kernel(ExpandArgs a) {
             const int pos = slot / a.nchunk, c = slot % a.nchunk;
             const int cnt = min(a.W, min(a.V, (c + 1) * a.chunk) - c * a.chunk);
             if (pos < cnt) {
-                const Cand cd = load_coherent(cands + (c * a.W + pos));
+                const Cand cd = cands[c * a.W + pos];
                 pe[u].key = (uint64_t)key_of(cd.val) << 32;  // inside a row the order of the raw logits
                 pe[u].tie = (uint32_t)cd.idx;
             }
@@ -417,11 +403,11 @@ __global__ __launch_bounds__(256) void attach_rows_kernel(ExpandArgs a) {
     // log-sum-exp of the row from the chunk statistics: wavefront 0, fixed summation order
     if (wave == 0) {
         float mx = -INFINITY;
-        for (int c = lane; c < a.nchunk; c += 64) mx = fmaxf(mx, load_coherent(stats + c).maxv);
+        for (int c = lane; c < a.nchunk; c += 64) mx = fmaxf(mx, stats[c].maxv);
         mx = float_of(wave_max_u32(key_of(mx)));
         double sum = 0.0;
         for (int c = lane; c < a.nchunk; c += 64) {
-            const ChunkStat st = load_coherent(stats + c);
+            const ChunkStat st = stats[c];
             if (st.maxv > -INFINITY) sum += st.sumexp * exp_nonpos((double)st.maxv - (double)mx);
         }
 #pragma unroll
@@ -537,7 +523,7 @@ ExpandPlan plan_expand(const ygg_shape& s, int32_t d) {
 
 // Static plus dynamic LDS of these two exceeds the 64 KiB default.
 hipError_t raise_limits_expand() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(expand_kernel<16>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(expand_merge_kernel<16>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_scratch_bytes(16));
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(attach_pool_kernel),
@@ -545,11 +531,18 @@ hipError_t raise_limits_expand() {
 }
 
 hipError_t launch_expand(const ExpandArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(expand_scan_kernel, dim3((unsigned)(a.B * a.F), (unsigned)a.nchunk), dim3(kScanThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     const int K = a.F * a.nchunk;
-    const dim3 grid((unsigned)(a.B * a.F), (unsigned)a.nchunk), block(kScanThreads);
-    if (K <= 256) hipLaunchKernelGGL(expand_kernel<1>, grid, block, merge_scratch_bytes(1), st, a);
-    else if (K <= 1024) hipLaunchKernelGGL(expand_kernel<4>, grid, block, merge_scratch_bytes(4), st, a);
-    else hipLaunchKernelGGL(expand_kernel<16>, grid, block, merge_scratch_bytes(16), st, a);
+    const dim3 grid((unsigned)a.B), block(256);
+    if (K <= 256) {
+        hipLaunchKernelGGL(expand_merge_kernel<1>, grid, block, merge_scratch_bytes(1), st, a);
+    } else if (K <= 1024) {
+        hipLaunchKernelGGL(expand_merge_kernel<4>, grid, block, merge_scratch_bytes(4), st, a);
+    } else {
+        hipLaunchKernelGGL(expand_merge_kernel<16>, grid, block, merge_scratch_bytes(16), st, a);
+    }
     return hipGetLastError();
 }
 
@@ -562,9 +555,11 @@ size_t attach_pool_bytes(const ygg_shape& s) {
 }
 
 hipError_t launch_attach(const ExpandArgs& a, hipStream_t st) {
+    hipLaunchKernelGGL(expand_scan_kernel, dim3((unsigned)(a.B * a.F), (unsigned)a.nchunk), dim3(kScanThreads), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     const int per_row = a.nchunk * a.W;
-    const dim3 rows((unsigned)(a.B * a.F), (unsigned)a.nchunk), block(256);
-    hipError_t e;
+    const dim3 rows((unsigned)(a.B * a.F)), block(256);
     if (per_row <= 256) hipLaunchKernelGGL(attach_rows_kernel<1>, rows, block, 0, st, a);
     else if (per_row <= 1024) hipLaunchKernelGGL(attach_rows_kernel<4>, rows, block, 0, st, a);
     else hipLaunchKernelGGL(attach_rows_kernel<16>, rows, block, 0, st, a);

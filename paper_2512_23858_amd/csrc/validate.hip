@@ -55,17 +55,7 @@ __global__ __launch_bounds__(256) void validate_logits_kernel(ValidateArgs a, in
     if (__any(bad) && (threadIdx.x & 63) == 0) atomicOr(&a.flags[b], (int)YGG_BAD_LOGIT);
 }
 
-__global__ __launch_bounds__(256) void zero_header_kernel(uint32_t* header) {
-    header[blockIdx.x * 256 + threadIdx.x] = 0u;
-}
-
 }  // namespace
-
-hipError_t launch_zero_header(uint32_t* header, hipStream_t st) {
-    static_assert(kHeaderCounters % 256 == 0, "whole workgroups");
-    hipLaunchKernelGGL(zero_header_kernel, dim3(kHeaderCounters / 256), dim3(256), 0, st, header);
-    return hipGetLastError();
-}
 
 hipError_t launch_validate(const ValidateArgs& a, hipStream_t st) {
     hipLaunchKernelGGL(validate_tree_kernel, dim3((unsigned)a.B), dim3(256), 0, st, a);

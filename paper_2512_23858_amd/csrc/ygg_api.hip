@@ -21,13 +21,12 @@ std::mutex g_init_mutex;
 
 // Library-owned workspace of ygg_equal_growth_expand_static, for callers that cannot provide one.  Every device
 // holds its own copy at its own address (looked up once per device, below); host code only ever uses that
-// address.  Zero at load, and every call leaves the header of arrival counters zero again.
+// address.  Nothing in it has to start at zero: every call writes what it reads.
 constexpr size_t kStaticScratchBytes = YGG_STATIC_SCRATCH_BYTES;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 unsigned char* g_scratch_ptr[kMaxDevices];
 
 inline size_t align256(size_t x) { return (x + 255) / 256 * 256; }
-constexpr size_t kHeaderBytes = YGG_WORKSPACE_HEADER_BYTES;
 
 bool common_shape_ok(const ygg_shape& s) {
     if (s.batch < 1 || s.batch > 65535) return false;
@@ -159,12 +158,6 @@ extern "C" {
 
 int32_t ygg_init(void) { return ensure_device_ready(); }
 
-int32_t ygg_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (int32_t rc = check_workspace(workspace, workspace_bytes, kHeaderBytes)) return rc;
-    return launch_zero_header(static_cast<uint32_t*>(workspace), static_cast<hipStream_t>(hip_stream)) == hipSuccess
-               ? YGG_OK : YGG_ERR_LAUNCH;
-}
-
 int32_t ygg_debug_set_attention_plan(int32_t waves, int32_t rblocks, int32_t nsplit, int32_t kshares) {
     if (waves < 0 || waves > 255 || rblocks < 0 || rblocks > 255 || kshares < 0 || kshares > 255 || nsplit < 0) return YGG_ERR_SHAPE;
     g_plan_override.store(((uint64_t)waves << 56) | ((uint64_t)rblocks << 48) | ((uint64_t)kshares << 40) | (uint32_t)nsplit,
@@ -199,22 +192,22 @@ size_t ygg_workspace_bytes(const ygg_shape* s, int32_t op, int32_t n_layers) {
         case YGG_OP_ATTENTION: {
             if (check_shape(s, true, false) != YGG_OK) return 0;
             const AttnPlan p = plan_attention(*s);
-            return kHeaderBytes + p.part_o_bytes + p.part_ml_bytes;
+            return p.part_o_bytes + p.part_ml_bytes;
         }
         case YGG_OP_EXPAND: {
             if (check_shape(s, false, true) != YGG_OK) return 0;
             const ExpandPlan p = plan_expand(*s, 2);  // the widest frontier
-            return kHeaderBytes + p.stat_bytes + p.cand_bytes;
+            return p.stat_bytes + p.cand_bytes;
         }
         case YGG_OP_ATTACH: {
             if (check_shape(s, false, true) != YGG_OK) return 0;
             const ExpandPlan p = plan_expand(*s, 2);
-            return kHeaderBytes + p.stat_bytes + p.cand_bytes + attach_offer_bytes(*s);
+            return p.stat_bytes + p.cand_bytes + attach_offer_bytes(*s);
         }
         case YGG_OP_ACCEPT: {
             if (check_shape(s, false, true) != YGG_OK) return 0;
             const AcceptPlan p = plan_accept(*s);
-            return kHeaderBytes + p.part_bytes + p.oldlen_bytes;
+            return p.part_bytes + p.oldlen_bytes;
         }
         default: return 0;
     }
@@ -232,14 +225,14 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     if ((int64_t)s->batch * s->n_nodes * s->n_q_heads > 0x7fffffffLL) return YGG_ERR_UNSUPPORTED;
     if (s->kv_capacity * s->n_kv_heads * s->head_dim * elem > 0xffffffffLL) return YGG_ERR_UNSUPPORTED;
     const AttnPlan p = plan_attention(*s);
-    if (int32_t rc = check_workspace(workspace, workspace_bytes, kHeaderBytes + p.part_o_bytes + p.part_ml_bytes)) return rc;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes)) return rc;
     if (int32_t rc = ensure_device_ready()) return rc;
 
     AttnArgs a{};
     a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.k_tree = k_tree; a.v_tree = v_tree;
     a.seq_lens = seq_lens; a.parent_idx = parent_idx; a.k_scale = k_scale; a.v_scale = v_scale;
-    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + kHeaderBytes);
-    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + kHeaderBytes + p.part_o_bytes);
+    a.part_o = static_cast<float*>(workspace);
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.part_o_bytes);
     a.out = out; a.lse = lse;
     a.B = s->batch; a.N = s->n_nodes; a.Hq = s->n_q_heads; a.Hkv = s->n_kv_heads;
     a.G = s->n_q_heads / s->n_kv_heads; a.Dh = s->head_dim;
@@ -299,15 +292,13 @@ int32_t ygg_equal_growth_expand(const ygg_shape* s, int32_t d, const float* draf
     if ((int64_t)p.F * p.nchunk > 4096) return YGG_ERR_UNSUPPORTED;  // merge holds <= 16 lists per thread
     if ((int64_t)p.F * s->vocab >= 0x7fffffffLL) return YGG_ERR_UNSUPPORTED;  // flat candidate index is 32 bits
     if ((int64_t)s->batch * p.F > 0x7fffffffLL || p.nchunk > 65535) return YGG_ERR_UNSUPPORTED;
-    if (s->batch > kHeaderCounters) return YGG_ERR_UNSUPPORTED;            // one arrival counter per sequence
-    if (int32_t rc = check_workspace(workspace, workspace_bytes, kHeaderBytes + p.stat_bytes + p.cand_bytes)) return rc;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.stat_bytes + p.cand_bytes)) return rc;
     if (int32_t rc = ensure_device_ready()) return rc;
 
     ExpandArgs a{};
     a.logits = draft_logits; a.parent_idx = parent_idx; a.token_ids = token_ids; a.cum_logprob = cum_logprob;
-    a.counters = static_cast<uint32_t*>(workspace);
-    a.stats = static_cast<char*>(workspace) + kHeaderBytes;
-    a.cands = static_cast<char*>(workspace) + kHeaderBytes + p.stat_bytes;
+    a.stats = workspace;
+    a.cands = static_cast<char*>(workspace) + p.stat_bytes;
     a.B = s->batch; a.D = s->depth; a.W = s->width; a.V = s->vocab; a.N = s->n_nodes; a.d = d;
     a.F = p.F; a.chunk = p.chunk; a.nchunk = p.nchunk;
     return launch_expand(a, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? YGG_OK : YGG_ERR_LAUNCH;
@@ -345,16 +336,14 @@ int32_t ygg_equal_growth_attach(const ygg_shape* s, int32_t t, const float* draf
     if ((int64_t)p.F * s->width + (int64_t)s->width * (s->depth - t + 1) > 4096) return YGG_ERR_UNSUPPORTED;
     if ((reinterpret_cast<uintptr_t>(pool) & 15u) != 0 || pool_bytes < attach_pool_bytes(*s)) return YGG_ERR_WORKSPACE;
     const size_t offer_bytes = attach_offer_bytes(*s);
-    if ((int64_t)s->batch * (p.F + 1) > kHeaderCounters) return YGG_ERR_UNSUPPORTED;  // one arrival counter per row
-    if (int32_t rc = check_workspace(workspace, workspace_bytes, kHeaderBytes + p.stat_bytes + p.cand_bytes + offer_bytes)) return rc;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.stat_bytes + p.cand_bytes + offer_bytes)) return rc;
     if (int32_t rc = ensure_device_ready()) return rc;
 
     ExpandArgs a{};
     a.logits = draft_logits; a.parent_idx = parent_idx; a.token_ids = token_ids; a.cum_logprob = cum_logprob;
-    a.counters = static_cast<uint32_t*>(workspace);
-    a.stats = static_cast<char*>(workspace) + kHeaderBytes;
-    a.cands = static_cast<char*>(workspace) + kHeaderBytes + p.stat_bytes;
-    a.offers = static_cast<char*>(workspace) + kHeaderBytes + p.stat_bytes + p.cand_bytes;
+    a.stats = workspace;
+    a.cands = static_cast<char*>(workspace) + p.stat_bytes;
+    a.offers = static_cast<char*>(workspace) + p.stat_bytes + p.cand_bytes;
     a.pool = pool; a.pool_cap = (int32_t)attach_pool_capacity(*s);
     a.B = s->batch; a.D = s->depth; a.W = s->width; a.V = s->vocab; a.N = s->n_nodes; a.d = t;
     a.F = p.F; a.chunk = p.chunk; a.nchunk = p.nchunk;
@@ -404,17 +393,15 @@ int32_t ygg_accept_and_compact(const ygg_shape* s, int32_t n_layers, const float
     if (n_layers > 0 && (!k_tree || !v_tree || !k_cache || !v_cache)) return YGG_ERR_NULL;
     const AcceptPlan p = plan_accept(*s);
     if ((int64_t)s->batch * s->n_nodes > 0x7fffffffLL || p.nchunk > 65535) return YGG_ERR_UNSUPPORTED;
-    if (s->batch > kHeaderCounters) return YGG_ERR_UNSUPPORTED;            // one arrival counter per sequence
-    if (int32_t rc = check_workspace(workspace, workspace_bytes, kHeaderBytes + p.part_bytes + p.oldlen_bytes)) return rc;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_bytes + p.oldlen_bytes)) return rc;
 
     AcceptArgs a{};
     a.target_logits = target_logits; a.target_tokens = target_tokens;
     a.parent_idx = parent_idx; a.token_ids = token_ids;
     a.k_tree = k_tree; a.v_tree = v_tree; a.k_cache = k_cache; a.v_cache = v_cache;
     a.seq_lens = seq_lens; a.accept_len = accept_len; a.accept_path = accept_path; a.bonus_token = bonus_token;
-    a.counters = static_cast<uint32_t*>(workspace);
-    a.part = static_cast<char*>(workspace) + kHeaderBytes;
-    a.old_len = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + kHeaderBytes + p.part_bytes);
+    a.part = workspace;
+    a.old_len = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + p.part_bytes);
     a.B = s->batch; a.N = s->n_nodes; a.D = s->depth; a.V = s->vocab; a.Hkv = s->n_kv_heads; a.Dh = s->head_dim;
     a.n_layers = n_layers; a.chunk = p.chunk; a.nchunk = p.nchunk; a.max_seq_len = s->max_seq_len;
     a.elem_bytes = s->kv_dtype == YGG_F32 ? 4 : s->kv_dtype == YGG_BF16 ? 2 : 1; a.cap = s->kv_capacity;

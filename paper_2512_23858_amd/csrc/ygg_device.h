@@ -39,54 +39,6 @@ __device__ __forceinline__ double double_of(uint64_t k) {
     return __longlong_as_double((long long)((k >> 63) ? (k & 0x7fffffffffffffffull) : ~k));
 }
 
-// ---- hand-off of small results between workgroups of one launch ------------------------------------
-// "The last workgroup to arrive finishes the job": producers write their partial results, then bump a
-// counter; whoever sees the final count reads every partial.  Ordinary stores may stay in the writing
-// XCD's L2 and ordinary loads may hit stale lines in the reader's, and a release/acquire fence pair at
-// device scope would write back and invalidate whole L2s.  Instead the partials themselves travel by
-// device-scope relaxed atomic stores and loads (write-through / always-coherent accesses of 8 bytes),
-// the producer waits for its stores to be acknowledged before the counter is touched, and the reader's
-// loads are issued only after the counter's value has come back.  Nothing waits or spins.
-__device__ __forceinline__ void store_coherent(uint64_t* p, uint64_t v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint64_t load_coherent(const uint64_t* p) {
-    return __hip_atomic_load(const_cast<uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename T>
-__device__ __forceinline__ void store_coherent(T* p, const T& v) {
-    static_assert(sizeof(T) % 8 == 0 && alignof(T) >= 8, "moved in 8-byte pieces");
-    uint64_t w[sizeof(T) / 8];
-    __builtin_memcpy(w, &v, sizeof(T));
-#pragma unroll
-    for (size_t i = 0; i < sizeof(T) / 8; ++i) store_coherent(reinterpret_cast<uint64_t*>(p) + i, w[i]);
-}
-template <typename T>
-__device__ __forceinline__ T load_coherent(const T* p) {
-    static_assert(sizeof(T) % 8 == 0 && alignof(T) >= 8, "moved in 8-byte pieces");
-    uint64_t w[sizeof(T) / 8];
-#pragma unroll
-    for (size_t i = 0; i < sizeof(T) / 8; ++i) w[i] = load_coherent(reinterpret_cast<const uint64_t*>(p) + i);
-    T v;
-    __builtin_memcpy(&v, w, sizeof(T));
-    return v;
-}
-// Called by every thread of the workgroup after its store_coherent calls.  Returns true in the workgroup
-// that arrives last of `total` (the counter must be 0 before the first arrival and is 0 again afterwards).
-// `flag` is one word of LDS.
-__device__ __forceinline__ bool arrive_and_check_last(uint32_t* counter, uint32_t total, uint32_t* flag) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this thread's stores have been acknowledged
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const bool last = old + 1 == total;
-        if (last) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *flag = last;
-    }
-    __syncthreads();
-    return *flag != 0;
-}
-
 // exp(t) for t <= 0 in fp64: k = round(t/ln 2), r = t - k ln 2 (two-part constant), Taylor series of
 // degree 13 on |r| <= ln(2)/2 (remainder < 1e-17), scaled by 2^k.  Relative error about 1e-16.
 __device__ __forceinline__ double exp_nonpos(double t) {

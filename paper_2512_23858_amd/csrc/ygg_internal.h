@@ -10,8 +10,6 @@ namespace ygg {
 constexpr int kMaxNodes = 1024;      // N limit (ancestor bitmasks and per-tree tables live in LDS)
 constexpr int kMaxWidth = 64;        // W limit (one wavefront holds a candidate list)
 constexpr int kKeyTile = 64;         // split boundaries of the key range are multiples of this
-// Every workspace starts with a header of arrival counters (YGG_WORKSPACE_HEADER_BYTES): zero between calls.
-constexpr int kHeaderCounters = YGG_WORKSPACE_HEADER_BYTES / 4;
 
 // ---- tree attention ---------------------------------------------------------------------------
 // Key index space of sequence b: [0, L_b) are cache rows, [L_b, L_b + N) are the tree's own rows.
@@ -60,7 +58,6 @@ hipError_t launch_attn_combine(const AttnArgs& a, const AttnPlan& p, int dtype, 
 hipError_t raise_limits_attn_mfma();
 hipError_t raise_limits_expand();
 int32_t ensure_device_ready();
-hipError_t launch_zero_header(uint32_t* header, hipStream_t st);  // fill kernel (graph-capturable, unlike a memset node)
 
 // ---- equal-growth expansion -------------------------------------------------------------------
 struct ExpandPlan {
@@ -75,7 +72,6 @@ struct ExpandArgs {
     int32_t* parent_idx;
     int32_t* token_ids;
     float* cum_logprob;
-    uint32_t* counters;  // arrival counters (workspace header): [B] per sequence, then [B*F] per row
     void* stats;
     void* cands;
     void* offers;      // free attachment only: [B*F][W] {double score; int32 node; int32 token}
@@ -137,7 +133,6 @@ struct AcceptArgs {
     int32_t* accept_len;
     int32_t* accept_path;
     int32_t* bonus_token;
-    uint32_t* counters;  // arrival counters (workspace header): [B]
     void* part;
     int32_t* old_len;
     int32_t B, N, D, V, Hkv, Dh, n_layers, chunk, nchunk, max_seq_len;

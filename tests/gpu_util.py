@@ -35,9 +35,8 @@ def shape_of(cfg: wl.Config, max_seq_len=None, kv_capacity=None, n_nodes=None) -
 def workspace(shape: ygg.Shape, op: int, n_layers: int = 0, poison: int = 0xA5) -> torch.Tensor:
     n = ygg.workspace_bytes(shape, op, n_layers)
     assert n > 0, "invalid shape for workspace query"
-    # poison the scratch space: kernels must not rely on its contents (0xFF bytes read as NaN); only the header of
-    # arrival counters is prepared, the way a caller prepares a fresh allocation
-    return ygg.workspace_init(torch.full((n,), poison, dtype=torch.uint8, device=DEV))
+    # poison the workspace: kernels must not rely on its contents (0xFF bytes read as NaN)
+    return torch.full((n,), poison, dtype=torch.uint8, device=DEV)
 
 
 def run_attention(shape: ygg.Shape, host: dict, parent_idx: np.ndarray, want_lse=True, poison: int = 0xA5):
