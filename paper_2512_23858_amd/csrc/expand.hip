@@ -80,22 +80,20 @@ __device__ __forceinline__ Entry wave_best(const Entry& e) {
 template <int N, typename Get>
 __device__ __forceinline__ void wave_top_w(Get get, int W, int wave, int lane, TopWShared& sh) {
     uint32_t cmax = 0;   // largest coarse key (top 32 bits) of this lane
-    int have = 0;        // candidates of this lane
+    int tot = 0;         // candidates of the wavefront
 #pragma unroll
     for (int k = 0; k < N; ++k) {
         const Entry e = get(k);
         cmax = max(cmax, (uint32_t)(e.key >> 32));
-        have += e.key != 0;
+        tot += (int)__popcll(__ballot(e.key != 0));
     }
-    int tot = have;      // candidates of the wavefront
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) tot += __shfl_xor(tot, o);
     const int want = min(W, tot);
     const int wn = min(W, (int)__popcll(__ballot(cmax != 0)));
-    // threshold: the wn-th largest lane maximum -- at least wn candidates lie at or above it
+    // threshold: at most the wn-th largest lane maximum, so at least wn candidates lie at or above it.  Its low
+    // twelve bits stay zero: a slightly lower threshold only pools a few more candidates.
     uint32_t t = 0;
     if (wn > 0) {
-        for (int bit = 31; bit >= 0; --bit) {
+        for (int bit = 31; bit >= 12; --bit) {
             const uint32_t c = t | (1u << bit);
             if ((int)__popcll(__ballot(cmax >= c)) >= wn) t = c;
         }
@@ -156,18 +154,33 @@ __device__ __forceinline__ void wave_top_w(Get get, int W, int wave, int lane, T
 __device__ __forceinline__ int merged_rank(const TopWShared& sh, int wave, int lane, Entry& mine) {
     if (lane >= sh.count[wave]) return -1;
     mine = sh.list[wave][lane];
-    int rank = lane;
+    // first position of each other list whose entry does not beat `mine`: three binary searches in step, so the
+    // three LDS reads of a round are in flight together
+    int lo[3], hi[3], cnt[3];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        if (w == wave) continue;
-        int lo = 0, hi = sh.count[w];  // first position whose entry does not beat `mine`
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (beats(sh.list[w][mid], mine)) lo = mid + 1; else hi = mid;
-        }
-        rank += lo;
+    for (int i = 0; i < 3; ++i) {
+        const int w = i + (i >= wave);
+        lo[i] = 0;
+        hi[i] = cnt[i] = sh.count[w];
     }
-    return rank;
+    for (int span = max(cnt[0], max(cnt[1], cnt[2])); span > 0; span >>= 1) {  // enough rounds for the longest list
+        Entry e[3];
+        int mid[3];
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int w = i + (i >= wave);
+            mid[i] = (lo[i] + hi[i]) >> 1;
+            e[i] = sh.list[w][min(mid[i], kMaxWidth - 1)];
+        }
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const bool open = lo[i] < hi[i];
+            const bool b = beats(e[i], mine);
+            lo[i] = open && b ? mid[i] + 1 : lo[i];
+            hi[i] = open && !b ? mid[i] : hi[i];
+        }
+    }
+    return lane + lo[0] + lo[1] + lo[2];
 }
 
 // ---- scan ---------------------------------------------------------------------------------------
@@ -200,9 +213,9 @@ __global__ __launch_bounds__(kScanThreads) void expand_scan_kernel(ExpandArgs a)
     const float cmax = fmaxf(fmaxf(red_f[0], red_f[1]), fmaxf(red_f[2], red_f[3]));
     double sum = 0.0;
     if (cmax > -INFINITY) {
+        // logits past the end of the chunk are -inf and add exactly 0; no branch, so the sixteen series interleave
 #pragma unroll
-        for (int k = 0; k < kScanElems; ++k)
-            if (w0 + k * 64 + lane < c1) sum += exp_nonpos((double)xv[k] - (double)cmax);
+        for (int k = 0; k < kScanElems; ++k) sum += exp_nonpos((double)xv[k] - (double)cmax);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
@@ -239,7 +252,7 @@ __global__ __launch_bounds__(kScanThreads) void expand_scan_kernel(ExpandArgs a)
 // ---- merge --------------------------------------------------------------------------------------
 constexpr size_t merge_scratch_bytes(int lpt) { return (size_t)256 * lpt * 12; }
 
-template <int LPT>  // chunk lists per thread
+template <int LPT, int EPT>  // chunk lists per thread; entries of the selected lists per thread (W*W <= 256*EPT)
 __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
     constexpr int KMAX = 256 * LPT;
     // scratch for the chunk statistics
@@ -283,16 +296,32 @@ __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
             cnt[u] = list_len(q);
         }
     }
+    if (tid < a.F) cum_s[tid] = (double)a.cum_logprob[(int64_t)b * a.N + base_prev + tid];
     __syncthreads();
-    if (tid < a.F) {
-        const int q0 = tid * a.nchunk;
-        float mx = -INFINITY;
-        for (int c = 0; c < a.nchunk; ++c) mx = fmaxf(mx, smax[q0 + c]);
-        double s = 0.0;
-        for (int c = 0; c < a.nchunk; ++c)
-            if (smax[q0 + c] > -INFINITY) s += ssum[q0 + c] * exp((double)smax[q0 + c] - (double)mx);
-        lse_s[tid] = (double)mx + log(s);
-        cum_s[tid] = (double)a.cum_logprob[(int64_t)b * a.N + base_prev + tid];
+    // a row's chunks go to a group of g lanes (g a power of two, small enough that all rows are in work at once
+    // where possible), 64/g rows per wavefront at a time; the summation order is fixed
+    {
+        int f2 = 1;
+        while (f2 < a.F) f2 <<= 1;
+        int g = 1;
+        while (g < a.nchunk && g < 64 && g * f2 < 256) g <<= 1;
+        const int rpw = 64 / g;
+        for (int p0 = wave * rpw; p0 < a.F; p0 += 4 * rpw) {
+            const int p = p0 + lane / g, cf = lane % g;
+            const int q0 = p * a.nchunk;
+            float mx = -INFINITY;
+            if (p < a.F)
+                for (int c = cf; c < a.nchunk; c += g) mx = fmaxf(mx, smax[q0 + c]);
+            for (int o = g >> 1; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            double s = 0.0;
+            if (p < a.F)
+                for (int c = cf; c < a.nchunk; c += g) {
+                    const float m = smax[q0 + c];
+                    if (m > -INFINITY) s += ssum[q0 + c] * exp_nonpos((double)m - (double)mx);
+                }
+            for (int o = g >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o);
+            if (p < a.F && cf == 0) lse_s[p] = (double)mx + log(s);
+        }
     }
     __syncthreads();
     auto entry_of = [&](uint32_t q, Cand cd) {  // fp64 score of candidate cd of list q
@@ -326,11 +355,10 @@ __global__ __launch_bounds__(256) void expand_merge_kernel(ExpandArgs a) {
     // 3. the W best entries of the selected lists are the new nodes.  The lists are sorted, so their
     //    entries are dealt out position-major (slot = pos * nsel + list, thread = slot mod 256): the
     //    strongest entries then sit in different lanes and the per-wavefront thresholds are tight.
-    //    Every thread fetches its (at most 16) entries in one batch of loads.
+    //    Every thread fetches its (at most EPT) entries in one batch of loads.
     __shared__ int sel_cnt[kMaxWidth];
     if (tid < nsel) sel_cnt[tid] = list_len((int)sel[tid]);
     __syncthreads();
-    constexpr int EPT = kMaxWidth * kMaxWidth / 256;  // 16
     auto get = [&](int u) {
         const int slot = tid + u * 256;
         Entry r = {0, kNone, 0};
@@ -521,13 +549,26 @@ ExpandPlan plan_expand(const ygg_shape& s, int32_t d) {
     return p;
 }
 
-// Static plus dynamic LDS of these two exceeds the 64 KiB default.
+// Static plus dynamic LDS of these exceeds the 64 KiB default.
 hipError_t raise_limits_expand() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(expand_merge_kernel<16>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_scratch_bytes(16));
-    if (e != hipSuccess) return e;
+    const void* big[] = {reinterpret_cast<const void*>(expand_merge_kernel<16, 1>),
+                         reinterpret_cast<const void*>(expand_merge_kernel<16, 4>),
+                         reinterpret_cast<const void*>(expand_merge_kernel<16, 16>)};
+    for (const void* f : big) {
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)merge_scratch_bytes(16));
+        if (e != hipSuccess) return e;
+    }
     return hipFuncSetAttribute(reinterpret_cast<const void*>(attach_pool_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)(4096 * sizeof(Entry)));
+}
+
+template <int LPT>
+static void launch_merge(const ExpandArgs& a, hipStream_t st) {
+    const dim3 grid((unsigned)a.B), block(256);
+    const size_t lds = merge_scratch_bytes(LPT);
+    if (a.W <= 16) hipLaunchKernelGGL((expand_merge_kernel<LPT, 1>), grid, block, lds, st, a);
+    else if (a.W <= 32) hipLaunchKernelGGL((expand_merge_kernel<LPT, 4>), grid, block, lds, st, a);
+    else hipLaunchKernelGGL((expand_merge_kernel<LPT, 16>), grid, block, lds, st, a);
 }
 
 hipError_t launch_expand(const ExpandArgs& a, hipStream_t st) {
@@ -535,14 +576,9 @@ hipError_t launch_expand(const ExpandArgs& a, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int K = a.F * a.nchunk;
-    const dim3 grid((unsigned)a.B), block(256);
-    if (K <= 256) {
-        hipLaunchKernelGGL(expand_merge_kernel<1>, grid, block, merge_scratch_bytes(1), st, a);
-    } else if (K <= 1024) {
-        hipLaunchKernelGGL(expand_merge_kernel<4>, grid, block, merge_scratch_bytes(4), st, a);
-    } else {
-        hipLaunchKernelGGL(expand_merge_kernel<16>, grid, block, merge_scratch_bytes(16), st, a);
-    }
+    if (K <= 256) launch_merge<1>(a, st);
+    else if (K <= 1024) launch_merge<4>(a, st);
+    else launch_merge<16>(a, st);
     return hipGetLastError();
 }
 

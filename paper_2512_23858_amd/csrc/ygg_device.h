@@ -41,10 +41,11 @@ __device__ __forceinline__ double double_of(uint64_t k) {
 
 // exp(t) for t <= 0 in fp64: k = round(t/ln 2), r = t - k ln 2 (two-part constant), Taylor series of
 // degree 13 on |r| <= ln(2)/2 (remainder < 1e-17), scaled by 2^k.  Relative error about 1e-16.
+// Branch-free (0 below the underflow point comes from a select), so independent calls interleave.
 __device__ __forceinline__ double exp_nonpos(double t) {
-    if (t < -745.0) return 0.0;
-    const double k = rint(t * 1.4426950408889634074);
-    double r = fma(k, -6.93147180369123816490e-01, t);
+    const double tc = fmax(t, -746.0);
+    const double k = rint(tc * 1.4426950408889634074);
+    double r = fma(k, -6.93147180369123816490e-01, tc);
     r = fma(k, -1.90821492927058770002e-10, r);
     double p = 1.0 / 6227020800.0;
     p = fma(p, r, 1.0 / 479001600.0);
@@ -60,7 +61,8 @@ __device__ __forceinline__ double exp_nonpos(double t) {
     p = fma(p, r, 0.5);
     p = fma(p, r, 1.0);
     p = fma(p, r, 1.0);
-    return ldexp(p, (int)k);
+    const double e = ldexp(p, (int)k);
+    return t < -745.0 ? 0.0 : e;
 }
 
 }  // namespace ygg
