@@ -678,19 +678,38 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 }
             if (a.lse && g2 == 0) a.lse[rg_of[rb]] = m_ref[rb] * kLn2 + logf(l_tot);
         } else {
-            // fp32 partial outputs (bf16 ones would halve this traffic, but rounding the partials and then the merged
-            // row costs up to a whole bf16 ulp, which outputs of magnitude 4 cannot afford inside 2e-2), written with
-            // streaming stores: they are read once, by the combine kernel, and leaving them dirty in L2 only lengthens
-            // the write-back at the end of this kernel
-            float* po = static_cast<float*>(a.part_o) + ((int64_t)split * rows_total + rg_of[rb]) * DH + 4 * g2;
+            // Partial outputs travel as fp16 relative to the row's largest magnitude c (kept in fp32 beside m and l):
+            // half the traffic of fp32 here and in the merge, an error of at most 2^-12 c per element whatever the
+            // range of V (bf16 partials would cost up to a whole bf16 ulp of the merged row, which outputs of
+            // magnitude 4 cannot afford inside 2e-2).  Streaming stores: the partials are read once, by the merge,
+            // and leaving them dirty in L2 only lengthens the write-back at the end of this kernel.
+            float rmax = 0.f;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int vq = 0; vq < 4; ++vq) {
-                    f32x4 val = {o[rb][db][4 * vq], o[rb][db][4 * vq + 1], o[rb][db][4 * vq + 2], o[rb][db][4 * vq + 3]};
-                    if constexpr (KV8) val *= v_unit;
-                    __builtin_nontemporal_store(val, reinterpret_cast<f32x4*>(po + 32 * db + 8 * vq));
+                for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, fabsf(o[rb][db][v]));
+            rmax = fmaxf(rmax, __shfl_xor(rmax, 32));
+            const float c = fmaxf(rmax, 1e-30f);
+            const float inv_c = 1.f / c;
+            // The two lanes of a row hold alternating groups of four head_dim positions; swapping halves between them
+            // (v_permlane32_swap) leaves each with eight consecutive ones, so a store covers 32 contiguous bytes of a row.
+            _Float16* po = reinterpret_cast<_Float16*>(a.part_o) + ((int64_t)split * rows_total + rg_of[rb]) * DH + 8 * g2;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int vp = 0; vp < 2; ++vp) {
+                    const f32x4 ve = {o[rb][db][8 * vp] * inv_c, o[rb][db][8 * vp + 1] * inv_c,
+                                      o[rb][db][8 * vp + 2] * inv_c, o[rb][db][8 * vp + 3] * inv_c};
+                    const f32x4 vo = {o[rb][db][8 * vp + 4] * inv_c, o[rb][db][8 * vp + 5] * inv_c,
+                                      o[rb][db][8 * vp + 6] * inv_c, o[rb][db][8 * vp + 7] * inv_c};
+                    const u32x2 he = __builtin_bit_cast(u32x2, __builtin_convertvector(ve, f16x4));
+                    const u32x2 ho = __builtin_bit_cast(u32x2, __builtin_convertvector(vo, f16x4));
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(he[0], ho[0], false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(he[1], ho[1], false, false);
+                    const u32x4 w = {s0[0], s1[0], s0[1], s1[1]};
+                    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(po + 32 * db + 16 * vp));
                 }
+            if (g2 == 0) a.part_c[(int64_t)split * rows_total + rg_of[rb]] = c * v_unit;  // KV8: V = v_scale * code value
             if (g2 == 0) {
                 float* pml = a.part_ml + ((int64_t)split * rows_total + rg_of[rb]) * 2;
                 pml[0] = m_ref[rb] * kLn2;  // natural-log units of the scaled scores

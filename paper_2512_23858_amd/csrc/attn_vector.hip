@@ -10,6 +10,7 @@
 #include "ygg_internal.h"
 
 #include <hip/hip_bf16.h>
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 #include <hip/hip_ext.h>
 
 namespace ygg {
@@ -156,7 +157,10 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(AttnArgs a) {
 // formed inside the group with shuffles; the partial outputs are then fetched for the live splits only, eight
 // loads in flight at a time (balanced batches leave most split indices of a row absent: m = -inf, slot of the
 // workspace never written).  m = +inf in split 0 marks a row whose final values the main kernel wrote itself.
-template <typename T, int DH>
+//
+// HALF: the partial outputs are the matrix-core kernels' (fp16, each row divided by its scale c, which is kept beside
+// m and l): split s then enters with weight w_s c_s instead of w_s; the normaliser is the same.
+template <typename T, int DH, bool HALF>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     constexpr int TPR = DH / 4;  // lanes per row: 32 or 16, a power of two that divides the wavefront
     constexpr int GS = 8;        // partial outputs in flight per lane
@@ -168,14 +172,16 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     constexpr int NH = 64 / TPR;          // records per lane: the host never plans more than 64 splits
     const int nsp = a.nsplit;
 
-    float m[NH], l[NH];
+    float m[NH], l[NH], cs[NH];
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
         const int sp = t + h * TPR;
         m[h] = -INFINITY;
         l[h] = 0.f;
+        cs[h] = 1.f;
         if (sp < nsp) {
             const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + ((int64_t)sp * rows + r) * 2);
+            if constexpr (HALF) cs[h] = a.part_c[(int64_t)sp * rows + r];  // (never written for an absent split: unused then)
             m[h] = ml.x;
             l[h] = ml.y;
         }
@@ -192,6 +198,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     for (int h = 0; h < NH; ++h) {
         w[h] = m[h] == -INFINITY ? 0.f : expf(m[h] - mstar);
         lstar = fmaf(l[h], w[h], lstar);
+        if constexpr (HALF) w[h] = w[h] == 0.f ? 0.f : w[h] * cs[h];  // from here on w weighs the stored partial output
     }
 #pragma unroll
     for (int o = TPR / 2; o > 0; o >>= 1) lstar += __shfl_xor(lstar, o, TPR);
@@ -199,7 +206,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < nsp; s0 += GS) {
         float ws[GS];
-        float4 v[GS];
+        float4 v[GS];   // HALF: the first two words hold the four fp16 values until every load of the batch is out
 #pragma unroll
         for (int u = 0; u < GS; ++u) {
             const int sp = s0 + u;   // its weight sits in lane sp % TPR of the group, slot sp / TPR
@@ -211,12 +218,25 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
             }
             ws[u] = sp >= nsp ? 0.f : wsel;
             v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ws[u] != 0.f) v[u] = *reinterpret_cast<const float4*>(a.part_o + ((int64_t)sp * rows + r) * DH + c);
+            if (ws[u] != 0.f) {
+                if constexpr (HALF) {
+                    const float2 raw = *reinterpret_cast<const float2*>(reinterpret_cast<const _Float16*>(a.part_o) + ((int64_t)sp * rows + r) * DH + c);
+                    v[u].x = raw.x;
+                    v[u].y = raw.y;
+                } else {
+                    v[u] = *reinterpret_cast<const float4*>(a.part_o + ((int64_t)sp * rows + r) * DH + c);
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < GS; ++u) {
-            acc[0] = fmaf(v[u].x, ws[u], acc[0]); acc[1] = fmaf(v[u].y, ws[u], acc[1]);
-            acc[2] = fmaf(v[u].z, ws[u], acc[2]); acc[3] = fmaf(v[u].w, ws[u], acc[3]);
+            float4 x = v[u];
+            if constexpr (HALF) {
+                const f16x4 hv = __builtin_bit_cast(f16x4, make_float2(v[u].x, v[u].y));
+                x = make_float4((float)hv[0], (float)hv[1], (float)hv[2], (float)hv[3]);
+            }
+            acc[0] = fmaf(x.x, ws[u], acc[0]); acc[1] = fmaf(x.y, ws[u], acc[1]);
+            acc[2] = fmaf(x.z, ws[u], acc[2]); acc[3] = fmaf(x.w, ws[u], acc[3]);
         }
     }
     if (!in_range) return;
@@ -247,10 +267,12 @@ hipError_t launch_combine_t(const AttnArgs& a, hipStream_t st) {
     const int64_t rows = (int64_t)a.B * a.N * a.Hq;
     if (a.Dh == 128) {
         dim3 grid((unsigned)((rows + 7) / 8));
-        hipLaunchKernelGGL((attn_combine_kernel<T, 128>), grid, dim3(256), 0, st, a);
+        if (a.part_half) hipLaunchKernelGGL((attn_combine_kernel<T, 128, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((attn_combine_kernel<T, 128, false>), grid, dim3(256), 0, st, a);
     } else {
         dim3 grid((unsigned)((rows + 15) / 16));
-        hipLaunchKernelGGL((attn_combine_kernel<T, 64>), grid, dim3(256), 0, st, a);
+        if (a.part_half) return hipErrorInvalidValue;  // the matrix-core kernels exist for head_dim 128 only
+        hipLaunchKernelGGL((attn_combine_kernel<T, 64, false>), grid, dim3(256), 0, st, a);
     }
     return hipGetLastError();
 }

@@ -130,8 +130,10 @@ AttnPlan plan_attention(const ygg_shape& s) {
         ns = (T + chunk - 1) / chunk;
     }
     p.nsplit = p.slots > 0 ? p.slots : (int32_t)ns;   // balanced batches: a sequence may span every run
-    p.part_o_bytes = align256((size_t)p.nsplit * (size_t)rows * (size_t)s.head_dim * sizeof(float));
+    // matrix-core kernels: fp16 partial outputs with one fp32 scale per row; vector kernel: fp32 partial outputs
+    p.part_o_bytes = align256((size_t)p.nsplit * (size_t)rows * (size_t)s.head_dim * (p.use_mfma ? 2 : 4));
     p.part_ml_bytes = align256((size_t)p.nsplit * (size_t)rows * 2 * sizeof(float));
+    p.part_c_bytes = p.use_mfma ? align256((size_t)p.nsplit * (size_t)rows * sizeof(float)) : 0;
     return p;
 }
 
@@ -192,7 +194,7 @@ size_t ygg_workspace_bytes(const ygg_shape* s, int32_t op, int32_t n_layers) {
         case YGG_OP_ATTENTION: {
             if (check_shape(s, true, false) != YGG_OK) return 0;
             const AttnPlan p = plan_attention(*s);
-            return p.part_o_bytes + p.part_ml_bytes;
+            return p.part_o_bytes + p.part_ml_bytes + p.part_c_bytes;
         }
         case YGG_OP_EXPAND: {
             if (check_shape(s, false, true) != YGG_OK) return 0;
@@ -225,7 +227,7 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     if ((int64_t)s->batch * s->n_nodes * s->n_q_heads > 0x7fffffffLL) return YGG_ERR_UNSUPPORTED;
     if (s->kv_capacity * s->n_kv_heads * s->head_dim * elem > 0xffffffffLL) return YGG_ERR_UNSUPPORTED;
     const AttnPlan p = plan_attention(*s);
-    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes)) return rc;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes + p.part_c_bytes)) return rc;
     if (int32_t rc = ensure_device_ready()) return rc;
 
     AttnArgs a{};
@@ -233,6 +235,8 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     a.seq_lens = seq_lens; a.parent_idx = parent_idx; a.k_scale = k_scale; a.v_scale = v_scale;
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.part_o_bytes);
+    a.part_c = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.part_o_bytes + p.part_ml_bytes);
+    a.part_half = p.use_mfma;
     a.out = out; a.lse = lse;
     a.B = s->batch; a.N = s->n_nodes; a.Hq = s->n_q_heads; a.Hkv = s->n_kv_heads;
     a.G = s->n_q_heads / s->n_kv_heads; a.Dh = s->head_dim;

@@ -45,10 +45,12 @@ def test_workspace_sizes():
     assert ygg.workspace_bytes(s, 7) == 0
     assert ygg.workspace_bytes(_shape(n_q_heads=7), ygg.OP_ATTENTION) == 0          # Hq % Hkv != 0
     assert ygg.workspace_bytes(_shape(kv_capacity=130), ygg.OP_ATTENTION) == 0      # < max_seq_len + D + 1
-    # the attention workspace holds one fp32 partial (Dh + 2 floats) per split and query row
+    # the attention workspace holds one partial per split and query row: Dh fp16 values and three floats (matrix-core
+    # kernels) or Dh + 2 floats (vector kernel)
     big = _shape(max_seq_len=32768, kv_capacity=32800)
     rows = big.batch * big.n_nodes * big.n_q_heads
-    assert ygg.workspace_bytes(big, ygg.OP_ATTENTION) >= rows * (128 + 2) * 4
+    per_row = 128 * 2 + 12 if ygg.attention_plan(big)["matrix_cores"] else (128 + 2) * 4
+    assert ygg.workspace_bytes(big, ygg.OP_ATTENTION) >= ygg.attention_plan(big)["key_splits"] * rows * per_row
 
 
 def _call_attention(shape, ptrs, ws=None, ws_bytes=0):
@@ -226,11 +228,13 @@ def test_attention_plans_of_the_five_configurations():
         got = ygg.attention_plan(s)
         for k, v in exp.items():
             assert got[k] == v, (c, k, got)
-    # the workspace follows the plan: one (Dh + 2)-float record per split and query row
+    # the workspace follows the plan: one record per split and query row (Dh fp16 values + three floats, or Dh + 2 floats)
     s2 = _shape(max_seq_len=4096, kv_capacity=4200)
     p = ygg.attention_plan(s2)
     rows = s2.batch * s2.n_nodes * s2.n_q_heads
-    assert ygg.workspace_bytes(s2, ygg.OP_ATTENTION) >= p["key_splits"] * rows * 130 * 4
+    per_row = 128 * 2 + 12 if p["matrix_cores"] else (128 + 2) * 4
+    need = p["key_splits"] * rows * per_row
+    assert need <= ygg.workspace_bytes(s2, ygg.OP_ATTENTION) < need + 3 * 256
 
 
 def test_plan_override_is_explicit_and_removable():
