@@ -32,13 +32,25 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (for the opt-in sanitizer test; a process
+    that loads it needs libasan preloaded and finds it through YGG_ORACLE_LIB)."""
+    out = os.path.join(_HERE, "libygg_oracle_san.so")
+    subprocess.check_call(
+        ["gcc", "-O1", "-g", "-fopenmp", "-fPIC", "-shared", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+         "-fno-omit-frame-pointer", "-o", out, _SRC, "-lm"]
+    )
+    return out
+
+
 _lib = None
 
 
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # YGG_ORACLE_LIB: another build of this same source (the sanitizer test's), never anything else
+        _lib = ctypes.CDLL(os.environ.get("YGG_ORACLE_LIB") or build())
         for name in (
             "ygg_oracle_attention_row",
             "ygg_oracle_tree_attention",
