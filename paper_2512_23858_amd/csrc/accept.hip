@@ -2,14 +2,17 @@
 // speculation management" stage that idles the GPU when it runs on the host; Sec. 4.1 under
 // Eq. 2: bonus token; Sec. 6: the TokenTree's K/V bookkeeping).
 //
-// Three kernels:
+// Two kernels:
 //   argmax_partial  grid (tree node, vocab chunk): coalesced 16-byte streaming of the verifier's
-//                   fp32 logits, first maximum per chunk.
-//   path_match      one workgroup per sequence: finishes the argmax, marks every node whose whole
-//                   root path matches, picks the deepest (lowest index on ties), writes the path,
-//                   the accepted length and the bonus token, and advances seq_lens.
-//   compact         grid (path slot, sequence, layer): copies the accepted nodes' K and V rows
-//                   behind the old end of the cache.
+//                   fp32 logits, first maximum per chunk; it also snapshots seq_lens into the
+//                   workspace (with the caller's own argmax tokens a one-workgroup kernel does that).
+//   match_compact   grid (path slot, sequence, layer group).  Every workgroup works the match of its
+//                   sequence out for itself -- finishes the argmax, marks every node whose whole root
+//                   path matches, picks the deepest (lowest index on ties) -- which costs less than a
+//                   kernel boundary would; the workgroup of slot 0 and layer group 0 writes the path,
+//                   the accepted length and the bonus token and advances seq_lens; then each workgroup
+//                   copies its slot's K and V rows behind the old end of the cache (read from the
+//                   snapshot: seq_lens itself may already have moved), layer by layer.
 #include "ygg_internal.h"
 
 namespace ygg {
@@ -24,6 +27,16 @@ __device__ __forceinline__ void take_first_max(float& v, int& i, float v2, int i
     if (v2 > v || (v2 == v && i2 < i)) { v = v2; i = i2; }
 }
 
+// The sequence's length before this call, clamped like everywhere else; the second kernel reads only this copy.
+__device__ __forceinline__ void snapshot_len(const AcceptArgs& a, int b) {
+    const int L = a.seq_lens[b];
+    a.old_len[b] = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
+}
+
+__global__ __launch_bounds__(256) void snapshot_kernel(AcceptArgs a) {
+    for (int b = threadIdx.x; b < a.B; b += 256) snapshot_len(a, b);
+}
+
 __global__ __launch_bounds__(256) void argmax_partial_kernel(AcceptArgs a) {
     __shared__ float sv[4];
     __shared__ int si[4];
@@ -33,6 +46,7 @@ __global__ __launch_bounds__(256) void argmax_partial_kernel(AcceptArgs a) {
     const int c0 = c * a.chunk;
     const int c1 = min(a.V, c0 + a.chunk);
     const float* x = a.target_logits + row * a.V;
+    if (c == 0 && tid == 0 && row % a.N == 0) snapshot_len(a, (int)(row / a.N));
 
     float bv = -INFINITY;
     int bi = 0x7fffffff;
@@ -67,14 +81,16 @@ __global__ __launch_bounds__(256) void argmax_partial_kernel(AcceptArgs a) {
     }
 }
 
-__global__ __launch_bounds__(256) void path_match_kernel(AcceptArgs a) {
+__global__ __launch_bounds__(256) void match_compact_kernel(AcceptArgs a) {
     __shared__ int parent_s[kMaxNodes];
     __shared__ int tstar_s[kMaxNodes];
     __shared__ int token_s[kMaxNodes];
     __shared__ unsigned long long best_s[4];
+    __shared__ int slot_node_s, len_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int b = blockIdx.x;
+    const int k_slot = blockIdx.x, b = blockIdx.y;
     const int N = a.N;
+    const int old_len = a.old_len[b];
 
     for (int i = tid; i < N; i += 256) {
         const int64_t node = (int64_t)b * N + i;
@@ -130,38 +146,42 @@ __global__ __launch_bounds__(256) void path_match_kernel(AcceptArgs a) {
         for (int w = 1; w < 4; ++w) key = best_s[w] > key ? best_s[w] : key;
         const int len = (int)(key >> 32);  // >= 1: the root always matches
         const int best = (int)(0xffffffffu - (unsigned)(key & 0xffffffffu));
+        const bool writer = k_slot == 0 && blockIdx.z == 0;
         int32_t* path = a.accept_path + (int64_t)b * (a.D + 1);
-        for (int k = len; k <= a.D; ++k) path[k] = -1;
-        int n = best;
+        if (writer)
+            for (int k = len; k <= a.D; ++k) path[k] = -1;
+        int n = best, mine = -1;
         for (int k = len - 1; k >= 0; --k) {
-            path[k] = n;
+            if (writer) path[k] = n;
+            if (k == k_slot) mine = n;
             n = parent_s[n];
         }
-        a.accept_len[b] = len;
-        a.bonus_token[b] = tstar_s[best];
-        int L = a.seq_lens[b];
-        L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
-        a.old_len[b] = L;
-        a.seq_lens[b] = L + len;
+        slot_node_s = mine;
+        len_s = len;
+        if (writer) {
+            a.accept_len[b] = len;
+            a.bonus_token[b] = tstar_s[best];
+            a.seq_lens[b] = old_len + len;
+        }
     }
-}
+    __syncthreads();
 
-__global__ __launch_bounds__(256) void compact_kernel(AcceptArgs a) {
-    const int k = blockIdx.x, b = blockIdx.y, layer = blockIdx.z;
-    if (k >= a.accept_len[b]) return;
-    const int node = a.accept_path[(int64_t)b * (a.D + 1) + k];
-    const int64_t dst_tok = (int64_t)a.old_len[b] + k;
-    if (node < 0 || node >= a.N || dst_tok < 0 || dst_tok >= a.cap) return;  // contract violations stay inside the buffers
+    // this workgroup's slot of the path: the node's K and V rows of every layer of its group go behind the old end
+    const int node = slot_node_s;
+    const int64_t dst_tok = (int64_t)old_len + k_slot;
+    if (k_slot >= len_s || node < 0 || node >= N || dst_tok >= a.cap) return;  // contract violations stay inside the buffers
     const int64_t row16 = (int64_t)a.Hkv * a.Dh * a.elem_bytes / 16;  // 16-byte units per token row
-    const int64_t src = (((int64_t)layer * a.B + b) * a.N + node) * row16;
-    const int64_t dst = (((int64_t)layer * a.B + b) * a.cap + dst_tok) * row16;
-    const uint4* ks = static_cast<const uint4*>(a.k_tree) + src;
-    const uint4* vs = static_cast<const uint4*>(a.v_tree) + src;
-    uint4* kd = static_cast<uint4*>(a.k_cache) + dst;
-    uint4* vd = static_cast<uint4*>(a.v_cache) + dst;
-    for (int64_t j = threadIdx.x; j < row16; j += 256) {
-        kd[j] = ks[j];
-        vd[j] = vs[j];
+    for (int layer = blockIdx.z; layer < a.n_layers; layer += gridDim.z) {
+        const int64_t src = (((int64_t)layer * a.B + b) * N + node) * row16;
+        const int64_t dst = (((int64_t)layer * a.B + b) * a.cap + dst_tok) * row16;
+        const uint4* ks = static_cast<const uint4*>(a.k_tree) + src;
+        const uint4* vs = static_cast<const uint4*>(a.v_tree) + src;
+        uint4* kd = static_cast<uint4*>(a.k_cache) + dst;
+        uint4* vd = static_cast<uint4*>(a.v_cache) + dst;
+        for (int64_t j = tid; j < row16; j += 256) {
+            kd[j] = ks[j];
+            vd[j] = vs[j];
+        }
     }
 }
 
@@ -185,15 +205,15 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
     hipError_t e;
     if (a.target_logits) {
         hipLaunchKernelGGL(argmax_partial_kernel, dim3((unsigned)(a.B * a.N), (unsigned)a.nchunk), dim3(256), 0, st, a);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else {
+        hipLaunchKernelGGL(snapshot_kernel, dim3(1), dim3(256), 0, st, a);
     }
-    hipLaunchKernelGGL(path_match_kernel, dim3((unsigned)a.B), dim3(256), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if (a.n_layers > 0) {
-        hipLaunchKernelGGL(compact_kernel, dim3((unsigned)(a.D + 1), (unsigned)a.B, (unsigned)a.n_layers), dim3(256), 0, st, a);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-    return hipSuccess;
+    // without layers only slot 0 runs (it writes the results); else up to eight workgroups share a slot's layers
+    const unsigned slots = a.n_layers > 0 ? (unsigned)(a.D + 1) : 1u;
+    const unsigned groups = a.n_layers > 8 ? 8u : (a.n_layers > 0 ? (unsigned)a.n_layers : 1u);
+    hipLaunchKernelGGL(match_compact_kernel, dim3(slots, (unsigned)a.B, groups), dim3(256), 0, st, a);
+    return hipGetLastError();
 }
 
 }  // namespace ygg
