@@ -694,6 +694,7 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
             // The two lanes of a row hold alternating groups of four head_dim positions; swapping halves between them
             // (v_permlane32_swap) leaves each with eight consecutive ones, so a store covers 32 contiguous bytes of a row.
             _Float16* po = reinterpret_cast<_Float16*>(a.part_o) + ((int64_t)split * rows_total + rg_of[rb]) * DH + 8 * g2;
+            u32x4 w[4][2];
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -706,9 +707,16 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                     const u32x2 ho = __builtin_bit_cast(u32x2, __builtin_convertvector(vo, f16x4));
                     const auto s0 = __builtin_amdgcn_permlane32_swap(he[0], ho[0], false, false);
                     const auto s1 = __builtin_amdgcn_permlane32_swap(he[1], ho[1], false, false);
-                    const u32x4 w = {s0[0], s1[0], s0[1], s1[1]};
-                    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(po + 32 * db + 16 * vp));
+                    w[db][vp] = u32x4{s0[0], s1[0], s0[1], s1[1]};
                 }
+            // the eight stores of a row leave back to back: neighbouring 32-byte pieces then combine into whole lines
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int vp = 0; vp < 2; ++vp)
+                    __builtin_nontemporal_store(w[db][vp], reinterpret_cast<u32x4*>(po + 32 * db + 16 * vp));
+            __builtin_amdgcn_sched_barrier(0);
             if (g2 == 0) a.part_c[(int64_t)split * rows_total + rg_of[rb]] = c * v_unit;  // KV8: V = v_scale * code value
             if (g2 == 0) {
                 float* pml = a.part_ml + ((int64_t)split * rows_total + rg_of[rb]) * 2;
