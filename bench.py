@@ -30,14 +30,15 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 FP32_VALU_PEAK_TFLOPS = 157.3
 HEADLINE = 4                    # the widest tree: where the metric's matrix-core half lives
 ALL_CONFIGS = (1, 2, 3, 5, 4)   # headline last
-# layers per step when all configurations run: enough distinct K/V to exceed the 256 MB last-level cache
-DEFAULT_LAYERS = {1: 1, 2: 32, 3: 32, 4: 8, 5: 4}
+# layers per step when all configurations run: the configurations' own 32 layers; the one-layer ones (1, 5) get
+# enough distinct K/V to exceed the 256 MB last-level cache
+DEFAULT_LAYERS = {1: 1, 2: 32, 3: 32, 4: 32, 5: 4}
 
 # HBM bytes per launch of the attention main kernel (FETCH_SIZE + WRITE_SIZE), measured offline with rocprofv3 --pmc
 # (a benchmark run cannot collect counters itself) by the commands in TRAFFIC_SOURCE, for the kernel as it stands in
 # the commit that file names.  Reported only together with that source.
 TRAFFIC_SOURCE = "profiles/attn_mfma_hbm_traffic.md"
-MEASURED_TRAFFIC_BYTES = {2: 26_434_253, 3: 38_260_019, 4: 178_742_272, 5: 406_039_142}
+MEASURED_TRAFFIC_BYTES = {2: 23626138, 3: 31027405, 4: 164346163, 5: 382484275}
 
 
 def attention_work(cfg, lens, kv_bytes=None):
