@@ -107,6 +107,25 @@ def test_bf16_short_prefix_and_tree_heavy(L, gain):
     _check(cfg, host, parent, max(L, 1))
 
 
+@pytest.mark.parametrize("v_scale", [2.0 ** -20, 2.0 ** 18])
+def test_bf16_split_partials_keep_their_precision_for_any_range_of_v(v_scale):
+    """Several key splits and V far outside what fp16 could hold as such (about 2.6e5) or far below its normal range:
+    the split partials are stored relative to each row's own magnitude, so the error bounds simply scale with V."""
+    cfg, host, parent = _inputs(_cfg(1, 8, 2, 6, 8, seed=95), [1500], 1500)
+    for name in ("v_cache", "v_tree"):   # a power of two: exact in bf16
+        host[name] = wl.to_storage((wl.storage_to_f64(host[name]) * v_scale).astype(np.float32), cfg.dtype)
+    ref_out, ref_lse = oracle.tree_attention(host["q"], host["k_cache"], host["v_cache"], host["seq_lens"],
+                                             host["k_tree"], host["v_tree"], parent, cfg.softmax_scale)
+    import paper_2512_23858_amd as ygg
+    shape = shape_of(cfg, max_seq_len=1500)
+    assert ygg.attention_plan(shape)["key_splits"] > 1
+    out, lse = run_attention(shape, host, parent)
+    assert np.isfinite(out).all()
+    err = np.abs(out - ref_out) / v_scale
+    assert err.max() <= 2e-2 and err.mean() <= 1e-2, (err.max(), err.mean())
+    assert np.abs(lse - ref_lse).max() <= 1e-3
+
+
 def test_bf16_chain_and_general_tree():
     N = 45
     for parent in (wl.chain_tree(N)[None], wl.random_topological_tree(5, N)[None]):
