@@ -12,7 +12,7 @@
 //                   kernel boundary would; the workgroup of slot 0 and layer group 0 writes the path,
 //                   the accepted length and the bonus token and advances seq_lens; then each workgroup
 //                   copies its slot's K and V rows behind the old end of the cache (read from the
-//                   snapshot: seq_lens itself may already have moved), layer by layer.
+//                   snapshot: seq_lens itself may already have moved), for its share of the layers.
 #include "ygg_internal.h"
 
 namespace ygg {
@@ -209,9 +209,13 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t st) {
         hipLaunchKernelGGL(snapshot_kernel, dim3(1), dim3(256), 0, st, a);
     }
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    // without layers only slot 0 runs (it writes the results); else up to eight workgroups share a slot's layers
+    // without layers only slot 0 runs (it writes the results); else a slot's layers are dealt out over as many
+    // workgroups as keep the grid near a thousand (each redoes the match; a workgroup's layers are copied one after another)
     const unsigned slots = a.n_layers > 0 ? (unsigned)(a.D + 1) : 1u;
-    const unsigned groups = a.n_layers > 8 ? 8u : (a.n_layers > 0 ? (unsigned)a.n_layers : 1u);
+    int64_t groups64 = 1024 / ((int64_t)slots * a.B);
+    if (groups64 > a.n_layers) groups64 = a.n_layers;
+    if (groups64 < 1) groups64 = 1;
+    const unsigned groups = (unsigned)groups64;
     hipLaunchKernelGGL(match_compact_kernel, dim3(slots, (unsigned)a.B, groups), dim3(256), 0, st, a);
     return hipGetLastError();
 }
