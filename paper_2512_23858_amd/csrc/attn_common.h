@@ -29,7 +29,8 @@ constexpr int ROWB = 256;  // bytes of one K or V row (head_dim 128, bf16) = 16 
 // The permutation is applied on the global side (which 16 bytes a lane fetches), never in LDS.
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kRescaleGap = 8.f;  // log2 units by which a row maximum may outgrow its softmax reference
+constexpr float kRescaleGap = 8.f;  // log2 units by which a row maximum may outgrow its softmax reference when one is taken
+constexpr float kWeightSumLimit = 1073741824.f;  // 2^30: a lane's 16 weights of one block may sum to this before the reference moves
 
 __device__ __forceinline__ i16x4 lds_read_tr16(const unsigned char* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p));

@@ -387,11 +387,13 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     // of block j) and a matrix phase (O^T += V^T.P^T of block j, then S^T of block j+1), so that the
     // two wavefronts resident on a SIMD keep its matrix pipe and its vector pipe busy in turn.
     //
-    // Softmax uses a per-row reference m_ref that is only raised when the running maximum exceeds
-    // it by more than kRescaleGap (in log2 units): p = 2^(x - m_ref) may then be as large as
-    // 2^kRescaleGap, which fp32 sums and bf16 weights hold without loss, and O and l -- which
-    // carry the same reference -- are rescaled only in that rare, wave-uniform branch.  The result
-    // O / l and lse = m_ref ln 2 + ln l do not depend on the reference.
+    // Softmax uses a per-row reference m_ref, set at the first block in which the row sees a key and
+    // raised only when a block's weights p = 2^(x - m_ref) sum to more than kWeightSumLimit: floating
+    // point keeps the relative precision of the weights (bf16) and of the sums (fp32) whatever their
+    // magnitude, so the common path takes no row maximum at all, and O and l -- which carry the same
+    // reference -- are rescaled only in that rare, wave-uniform branch.  Scores far below the
+    // reference underflow to weight 0, which is what they are worth next to the key that set it.  The
+    // result O / l and lse = m_ref ln 2 + ln l do not depend on the reference.
     const int j16 = lane & 15;
     // K operand of step s: row n, slot 2s+g2 -> slot' = (2s+g2) ^ (n&15) = 2*(s ^ (n&15)>>1) + (g2 ^ (n&1))
     const int k_lane_off = n * ROWB + 16 * (g2 ^ (n & 1));
@@ -463,11 +465,38 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 for (int v = 0; v < 16; ++v)
                     if (!((okmask >> (8 * (v >> 2) + (v & 3))) & 1u)) st[rb][v] = -INFINITY;
             }
-            float mt = st[rb][0];
+            // weights of this lane's 16 keys relative to the reference ms, packed for the P.V product; returns their sum
+            auto weights = [&](float ms) __attribute__((always_inline)) {
+                float ps = 0.f;
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mt = fmaxf(mt, st[rb][v]);
-            mt *= c_scale;  // c_scale > 0: the maximum commutes with the scaling
-            if (__any(mt > m_ref[rb] + kRescaleGap)) {
+                for (int m2 = 0; m2 < 2; ++m2) {
+                    union { bf16x2 h[4]; i16x8 v; } pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(st[rb][8 * m2 + 2 * e], c_scale, -ms));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(st[rb][8 * m2 + 2 * e + 1], c_scale, -ms));
+                        ps += p0;
+                        ps += p1;
+                        const f32x2 pr = {p0, p1};
+                        pk.h[e] = __builtin_convertvector(pr, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
+                    }
+                    pb[rb][m2] = pk.v;
+                }
+                return ps;
+            };
+            // Common case: the row has a reference and no weight comes out large -- no maximum is taken at all.
+            bool move = __any(m_ref[rb] == -INFINITY);  // a row without a reference yet (nothing visible so far)
+            float ps = 0.f;
+            if (!move) {
+                ps = weights(m_ref[rb]);
+                move = __any(!(ps <= kWeightSumLimit));  // scores that outgrew the reference
+            }
+            if (move) {
+                // Rare, wave-uniform: set or raise the reference from the block's row maxima, rescale what has been summed.
+                float mt = st[rb][0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) mt = fmaxf(mt, st[rb][v]);
+                mt *= c_scale;  // c_scale > 0: the maximum commutes with the scaling
                 const float row_max = fmaxf(mt, __shfl_xor(mt, 32));
                 const bool raise = row_max > m_ref[rb] + kRescaleGap;  // same answer in both half-lanes of a row
                 const float alpha = raise ? __builtin_amdgcn_exp2f(m_ref[rb] - row_max) : 1.f;
@@ -477,25 +506,9 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[rb][db][v] *= alpha;
-            }
-            const float ms = m_ref[rb] == -INFINITY ? 0.f : m_ref[rb];  // row with nothing visible so far
-            float ps = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                st[rb][v] = __builtin_amdgcn_exp2f(fmaf(st[rb][v], c_scale, -ms));
-                ps += st[rb][v];
+                ps = weights(m_ref[rb] == -INFINITY ? 0.f : m_ref[rb]);  // the scores are still in st
             }
             l_run[rb] += ps;
-#pragma unroll
-            for (int m2 = 0; m2 < 2; ++m2) {
-                union { bf16x2 h[4]; i16x8 v; } pk;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const f32x2 pr = {st[rb][8 * m2 + 2 * e], st[rb][8 * m2 + 2 * e + 1]};
-                    pk.h[e] = __builtin_convertvector(pr, bf16x2);  // v_cvt_pk_bf16_f32, round to nearest even
-                }
-                pb[rb][m2] = pk.v;
-            }
         }
     };
 

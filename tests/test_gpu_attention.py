@@ -126,6 +126,19 @@ def test_bf16_split_partials_keep_their_precision_for_any_range_of_v(v_scale):
     assert np.abs(lse - ref_lse).max() <= 1e-3
 
 
+@pytest.mark.parametrize("lens,max_len", [([700], 700), ([900, 130, 415], 900)])
+def test_bf16_scores_far_above_and_below_the_softmax_reference(lens, max_len):
+    """The kernel keeps a per-row softmax reference that only moves when a block's weights outgrow it by 2^30.  Here
+    the first keys of the prefix score far above the bulk (everything after them underflows against the reference
+    they set) and the tree's own keys, which come last, far above those again (the reference has to move mid-stream,
+    with the accumulated output rescaled)."""
+    cfg, host, parent = _inputs(_cfg(len(lens), 8, 2, 6, 8, seed=96), lens, max_len, tree_gain=14.0)
+    k = wl.storage_to_f64(host["k_cache"])
+    k[:, :40] *= 9.0
+    host["k_cache"] = wl.to_storage(k.astype(np.float32), cfg.dtype)
+    _check(cfg, host, parent, max_len)
+
+
 def test_bf16_chain_and_general_tree():
     N = 45
     for parent in (wl.chain_tree(N)[None], wl.random_topological_tree(5, N)[None]):
