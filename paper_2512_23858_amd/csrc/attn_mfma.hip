@@ -275,12 +275,14 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     auto fill_tile = [&](int buf, int tile_base) {
         if (wave >= FILLERS) return;
         const uint32_t kdst0 = k_lds + buf * TILEB + wave * 1024, vdst0 = v_lds + buf * TILEB + wave * 1024;
-        if (tile_base + KT <= min(L, k1)) {  // a whole tile of cache rows: base + constant per-lane offsets
-            const uint32_t base = (uint32_t)tile_base * tok_bytes;
+        if (tile_base + KT <= min(L, k1)) {  // a whole tile of cache rows: the tile's base joins the scalar pointer,
+            // the per-lane offsets are constants of the kernel (no vector arithmetic per load)
+            const unsigned char* kc_t = uniform_ptr(kc + (size_t)((uint32_t)tile_base * tok_bytes));
+            const unsigned char* vc_t = uniform_ptr(vc + (size_t)((uint32_t)tile_base * tok_bytes));
 #pragma unroll
             for (int it = 0; it < FPW; ++it) {
-                dma_load16<NT>(kc, base + fill_k[it], __builtin_amdgcn_readfirstlane(kdst0 + it * FILLERS * 1024));
-                dma_load16<NT>(vc, base + fill_v[it], __builtin_amdgcn_readfirstlane(vdst0 + it * FILLERS * 1024));
+                dma_load16<NT>(kc_t, fill_k[it], __builtin_amdgcn_readfirstlane(kdst0 + it * FILLERS * 1024));
+                dma_load16<NT>(vc_t, fill_v[it], __builtin_amdgcn_readfirstlane(vdst0 + it * FILLERS * 1024));
             }
             return;
         }
