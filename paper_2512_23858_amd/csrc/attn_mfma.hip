@@ -155,6 +155,34 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
 
     for (int b = b_first; b <= b_last; ++b) {
     if (balanced && b != b_first) __syncthreads();   // the previous segment's tile buffers and masks are free again
+    // rows of this lane: block rb of this wave -> row_base + (wrow*RB + rb)*32 + n
+    int rg_of[RB];       // global row index (b, node, q head) or -1; fits 31 bits (checked on the host)
+    int node_of[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        const int row = row_base + (wrow * RB + rb) * 32 + n;
+        const int i = min(row, R - 1) / a.G;
+        const int g = min(row, R - 1) % a.G;
+        node_of[rb] = i;
+        rg_of[rb] = row < R && !is_loader ? (b * a.N + i) * a.Hq + hk * a.G + g : -1;
+    }
+
+    // (issued before the sequence length is first needed: the rows do not depend on it, and the length is a
+    // dependent load from device memory at the head of every workgroup's critical path)
+    // Q as the B operand of S^T = K.Q^T: lane (n, g2) holds Q[row n][16 s + 8 g2 .. +8) for s = 0..7
+    bf16x8 qreg[RB][8];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+        if (rg_of[rb] >= 0) {
+            const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const uint16_t*>(a.q) + (int64_t)rg_of[rb] * DH + 8 * g2);
+#pragma unroll
+            for (int s = 0; s < 8; ++s) qreg[rb][s] = qp[2 * s];
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) qreg[rb][s] = bf16x8{};
+        }
+    }
+
     int L = a.seq_lens[b];
     L = L < 0 ? 0 : (L > a.max_seq_len ? a.max_seq_len : L);
     const int Tk = L + a.N;
@@ -196,18 +224,6 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     }
     [&]() {   // one segment; wavefronts that have nothing more to do leave through `return`
 
-    // rows of this lane: block rb of this wave -> row_base + (wrow*RB + rb)*32 + n
-    int rg_of[RB];       // global row index (b, node, q head) or -1; fits 31 bits (checked on the host)
-    int node_of[RB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        const int row = row_base + (wrow * RB + rb) * 32 + n;
-        const int i = min(row, R - 1) / a.G;
-        const int g = min(row, R - 1) % a.G;
-        node_of[rb] = i;
-        rg_of[rb] = row < R && !is_loader ? (b * a.N + i) * a.Hq + hk * a.G + g : -1;
-    }
-
     if (k0 >= k1) {  // empty split (uniform over the workgroup): mark the partials as absent
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
@@ -217,20 +233,6 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 pml[1] = 0.f;
             }
         return;
-    }
-
-    // Q as the B operand of S^T = K.Q^T: lane (n, g2) holds Q[row n][16 s + 8 g2 .. +8) for s = 0..7
-    bf16x8 qreg[RB][8];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-        if (rg_of[rb] >= 0) {
-            const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const uint16_t*>(a.q) + (int64_t)rg_of[rb] * DH + 8 * g2);
-#pragma unroll
-            for (int s = 0; s < 8; ++s) qreg[rb][s] = qp[2 * s];
-        } else {
-#pragma unroll
-            for (int s = 0; s < 8; ++s) qreg[rb][s] = bf16x8{};
-        }
     }
 
     // ancestor bitmasks of the nodes this workgroup's rows belong to
