@@ -85,7 +85,11 @@ AttnPlan plan_attention(const ygg_shape& s) {
             p.waves = 8;
             int best = padded(256);
             if (padded(128) * 100 <= best * 85) { best = padded(128); p.kshares = 2; }
-            if (padded(192) * 100 <= best * 80) { p.waves = 6; p.kshares = 1; }
+            // 192 rows: two of the four SIMDs carry one wavefront only, so against 256-row workgroups it has to save a
+            // fifth of the rows (config 4 with 1344 instead of 1536 padded rows: 210 vs 202 us); against the paired
+            // 128-row shape, which meets a barrier every 16 matrix instructions, a tenth is enough (config 3 with 576
+            // instead of 640 padded rows and 10 instead of 6 key splits: 27.5 vs 28.1 us per call)
+            if (padded(192) * 100 <= best * (p.kshares == 2 ? 92 : 80)) { p.waves = 6; p.kshares = 1; }
         }
         int64_t ns_forced = 0;
         if (const uint64_t ov = g_plan_override.load(std::memory_order_relaxed)) {

@@ -215,7 +215,7 @@ def test_attention_plans_of_the_five_configurations():
     import ygg_workloads as wl
     want = {1: dict(matrix_cores=False),
             2: dict(matrix_cores=True, waves=4, key_shares=2, row_tiles=1, key_splits=6),
-            3: dict(matrix_cores=True, waves=8, key_shares=2, row_tiles=5, key_splits=6),
+            3: dict(matrix_cores=True, waves=6, key_shares=1, row_tiles=3, key_splits=10),
             4: dict(matrix_cores=True, waves=8, key_shares=1, row_tiles=6, key_splits=5),
             # a batch: 16 equal runs of the concatenated key tiles per (kv head, row tile) = 256 workgroups
             5: dict(matrix_cores=True, waves=8, key_shares=1, row_tiles=2, key_splits=16)}
