@@ -603,10 +603,13 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     i16x8 va[4][2];
     f32x16 st[RB];
     i16x8 pb[RB][2];
-    int buf = 0;
-    auto body = [&](int t) {
+    // Tile t lives in buffer t % NBUF.  The loop is unrolled NBUF-fold with the buffer index a compile-time constant, so
+    // that every LDS operand address is a loop-invariant per-lane register plus an immediate (no address arithmetic
+    // per block).
+    auto body = [&](int t, auto bufc) __attribute__((always_inline)) {
+        constexpr int buf = decltype(bufc)::value;
+        constexpr int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
         const int tile_base = k0 + t * KT;
-        const int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
         const bool clean = tile_base + KT <= clean_end;
         if constexpr (KS == 1) {
             // block 0 of the tile
@@ -633,11 +636,20 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
         pv(va, pb);
         if (t + 1 < ntiles) qk(ka, st);
         __builtin_amdgcn_sched_barrier(0);
-        buf = buf_next;
     };
     read_k(0, kh, ka);
     qk(ka, st);
-    for (int t = 0; t < ntiles; ++t) body(t);
+    static_assert(NBUF == 3, "the unrolling below names the three buffers");
+    int t = 0;
+    for (; t + 3 <= ntiles; t += 3) {
+        body(t, IntC<0>{});
+        body(t + 1, IntC<1>{});
+        body(t + 2, IntC<2>{});
+    }
+    if (t < ntiles) {
+        body(t, IntC<0>{});
+        if (t + 1 < ntiles) body(t + 1, IntC<1>{});
+    }
     if constexpr (KS == 2) {
         // Merge of the two key shares of a row block.  Both carry O~ and l relative to their own
         // reference m_ref; the share of block 1 hands its state over through the (now idle) tile
