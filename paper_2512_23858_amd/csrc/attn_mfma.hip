@@ -204,19 +204,9 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
         if (t0 >= t1) continue;   // (cannot happen for b_first .. b_last; keeps a wrong split index out of the workspace)
         split = slot - s_first;
         direct = s_first == s_last;
-        if (slot == s_first && tid < 256) {
-            // first segment of this sequence: tell the merge which split indices exist for this row tile's rows --
-            // either "already final" (m = +inf in index 0) or "absent" (m = -inf) beyond the last segment
-            for (int r = tid; r < min(RW, R - row_base); r += 256) {
-                const int row = row_base + r;
-                const int64_t rg = ((int64_t)b * a.N + row / a.G) * a.Hq + hk * a.G + row % a.G;
-                for (int sp = direct ? 0 : s_last - s_first + 1; sp < a.nsplit; ++sp) {
-                    float* pml = a.part_ml + ((int64_t)sp * rows_total + rg) * 2;
-                    pml[0] = direct && sp == 0 ? INFINITY : -INFINITY;
-                    pml[1] = 0.f;
-                }
-            }
-        }
+        // the workgroup of kv head 0 and row tile 0 that holds the sequence's first tile tells the merge how many runs the
+        // sequence fell into (the run boundaries are the same for every kv head and row tile)
+        if (slot == s_first && hk == 0 && rt == 0 && tid == 0) a.seq_splits[b] = direct ? 0 : s_last - s_first + 1;
     }
     if constexpr (balanced) {
         k0 = uni(k0); k1 = uni(k1); split = uni(split); L = uni(L);

@@ -154,9 +154,10 @@ __global__ __launch_bounds__(256) void attn_vector_kernel(AttnArgs a) {
 // O = sum_s O~_s e^{m_s - m*} / l*, lse = m* + ln l*.
 // A group of DH/4 lanes owns one row, each lane four output elements.  The (m, l) records are read once per
 // row -- lane t of the group takes splits t and t + DH/4 -- and the maximum, the weights e^{m_s - m*} and l* are
-// formed inside the group with shuffles; the partial outputs are then fetched for the live splits only, eight
-// loads in flight at a time (balanced batches leave most split indices of a row absent: m = -inf, slot of the
-// workspace never written).  m = +inf in split 0 marks a row whose final values the main kernel wrote itself.
+// formed inside the group with shuffles; the partial outputs are then fetched for the live splits only (m = -inf
+// marks an empty split, whose row of the workspace was never written), eight loads in flight at a time.  Balanced
+// batches: a sequence's splits are the runs its keys fell into, seq_splits[b] of them (a table the main kernel
+// fills); 0 means one run held the whole sequence and the main kernel wrote its final rows itself.
 //
 // HALF: the partial outputs are the matrix-core kernels' (fp16, each row divided by its scale c, which is kept beside
 // m and l): split s then enters with weight w_s c_s instead of w_s; the normaliser is the same.
@@ -170,7 +171,11 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     const int64_t r = in_range ? r_raw : rows - 1;
     const int t = threadIdx.x % TPR, c = 4 * t;
     constexpr int NH = 64 / TPR;          // records per lane: the host never plans more than 64 splits
-    const int nsp = a.nsplit;
+    int nsp = a.nsplit;
+    if (a.seq_splits) {  // balanced batches: the sequence's own number of runs; 0 = its rows are final already
+        nsp = a.seq_splits[r / ((int64_t)a.N * a.Hq)];
+        if (nsp == 0) return;  // (the whole group agrees: same row)
+    }
 
     float m[NH], l[NH], cs[NH];
 #pragma unroll
@@ -186,7 +191,6 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
             l[h] = ml.y;
         }
     }
-    if (__shfl(m[0], 0, TPR) == INFINITY) return;  // final already (the whole group agrees: same row)
     float mstar = m[0];
 #pragma unroll
     for (int h = 1; h < NH; ++h) mstar = fmaxf(mstar, m[h]);

@@ -138,6 +138,7 @@ AttnPlan plan_attention(const ygg_shape& s) {
     p.part_o_bytes = align256((size_t)p.nsplit * (size_t)rows * (size_t)s.head_dim * (p.use_mfma ? 2 : 4));
     p.part_ml_bytes = align256((size_t)p.nsplit * (size_t)rows * 2 * sizeof(float));
     p.part_c_bytes = p.use_mfma ? align256((size_t)p.nsplit * (size_t)rows * sizeof(float)) : 0;
+    p.seq_splits_bytes = p.slots > 0 ? align256((size_t)s.batch * sizeof(int32_t)) : 0;
     return p;
 }
 
@@ -198,7 +199,7 @@ size_t ygg_workspace_bytes(const ygg_shape* s, int32_t op, int32_t n_layers) {
         case YGG_OP_ATTENTION: {
             if (check_shape(s, true, false) != YGG_OK) return 0;
             const AttnPlan p = plan_attention(*s);
-            return p.part_o_bytes + p.part_ml_bytes + p.part_c_bytes;
+            return p.part_o_bytes + p.part_ml_bytes + p.part_c_bytes + p.seq_splits_bytes;
         }
         case YGG_OP_EXPAND: {
             if (check_shape(s, false, true) != YGG_OK) return 0;
@@ -231,7 +232,7 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     if ((int64_t)s->batch * s->n_nodes * s->n_q_heads > 0x7fffffffLL) return YGG_ERR_UNSUPPORTED;
     if (s->kv_capacity * s->n_kv_heads * s->head_dim * elem > 0xffffffffLL) return YGG_ERR_UNSUPPORTED;
     const AttnPlan p = plan_attention(*s);
-    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes + p.part_c_bytes)) return rc;
+    if (int32_t rc = check_workspace(workspace, workspace_bytes, p.part_o_bytes + p.part_ml_bytes + p.part_c_bytes + p.seq_splits_bytes)) return rc;
     if (int32_t rc = ensure_device_ready()) return rc;
 
     AttnArgs a{};
@@ -240,6 +241,7 @@ static int32_t tree_attention_impl(const ygg_shape* s, const void* q, const void
     a.part_o = static_cast<float*>(workspace);
     a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.part_o_bytes);
     a.part_c = reinterpret_cast<float*>(static_cast<char*>(workspace) + p.part_o_bytes + p.part_ml_bytes);
+    a.seq_splits = p.slots > 0 ? reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + p.part_o_bytes + p.part_ml_bytes + p.part_c_bytes) : nullptr;
     a.part_half = p.use_mfma;
     a.out = out; a.lse = lse;
     a.B = s->batch; a.N = s->n_nodes; a.Hq = s->n_q_heads; a.Hkv = s->n_kv_heads;

@@ -30,6 +30,8 @@ struct AttnArgs {
     float* part_o;    // [nsplit][B*N*Hq][Dh]  fp32 O~, or (part_half) fp16 O~ / part_c: same indexing, half the bytes
     float* part_ml;   // [nsplit][B*N*Hq][2]   (running max m in scaled-score units, sum l)
     float* part_c;    // [nsplit][B*N*Hq]      part_half only: the row's scale, max |O~| over head_dim
+    int32_t* seq_splits;  // [B], balanced batches only: how many runs a sequence's keys fell into (its partials carry split
+                          // indices 0 .. n-1), or 0 if one run held it all and its rows are final already
     int32_t part_half;  // 1: the matrix-core kernels' partial outputs (fp16, scaled per row); 0: the vector kernel's fp32 ones
     void* out;
     float* lse;
@@ -48,7 +50,7 @@ struct AttnPlan {
     int32_t kshares;        // MFMA kernel: 1, or 2 = pairs of wavefronts split every key tile
     int32_t row_tiles;      // MFMA kernel: workgroups along the N*G query rows of one kv head
     int32_t slots;          // MFMA kernel, batches: equal runs of key tiles per (kv head, row tile); 0 = one sequence per workgroup
-    size_t part_o_bytes, part_ml_bytes, part_c_bytes;
+    size_t part_o_bytes, part_ml_bytes, part_c_bytes, seq_splits_bytes;
 };
 
 AttnPlan plan_attention(const ygg_shape& s);
