@@ -7,7 +7,10 @@
 // worth more than its parent, so the k most valuable nodes (equal values: lower index, i.e. the
 // parent, first) are already a connected set that contains the root, and they are optimal for
 // every k at once: the programme collapses to one sort, and the optimal sets for all widths are
-// nested prefixes of that order.  One workgroup per sequence sorts the N <= 1024 keys in LDS.
+// nested prefixes of that order.  One workgroup per sequence orders the N <= 1024 keys in LDS: by
+// counting, for each key, the larger ones (N <= 512), else with a bitonic sort.
+#include <type_traits>
+
 #include "ygg_device.h"
 #include "ygg_internal.h"
 
@@ -30,9 +33,39 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(PruneArgs a, int n2) {
     const float* cum = a.cum_logprob + (int64_t)b * N;
     const int32_t* parent = a.parent_idx + (int64_t)b * N;
 
-    for (int i = tid; i < n2; i += kThreads)
+    for (int i = tid; i < max(n2, 8); i += kThreads)
         key[i] = i < N ? ((uint64_t)key_of(cum[i]) << 32) | (uint32_t)(0xffffffffu - (uint32_t)i) : 0ull;
     __syncthreads();
+    if (N <= 2 * kThreads) {
+        // One or two keys per thread: a key's place in the order is the number of larger keys (the keys are distinct: the
+        // index sits in their low bits; the padding zeros are smaller than any key).  N broadcast reads from LDS, eight in
+        // flight, instead of the sort's log^2 rounds of dependent exchanges.
+        auto count_sort = [&](auto kptc) __attribute__((always_inline)) {
+            constexpr int KPT = decltype(kptc)::value;
+            uint64_t mine[KPT];
+            int rank[KPT];
+#pragma unroll
+            for (int q = 0; q < KPT; ++q) {
+                const int i = tid + q * kThreads;
+                mine[q] = i < N ? key[i] : 0ull;
+                rank[q] = 0;
+            }
+            for (int j = 0; j < n2; j += 8) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const uint64_t x = key[j + u];
+#pragma unroll
+                    for (int q = 0; q < KPT; ++q) rank[q] += x > mine[q];
+                }
+            }
+            __syncthreads();  // every thread has read the unsorted keys
+#pragma unroll
+            for (int q = 0; q < KPT; ++q)
+                if (tid + q * kThreads < N) key[rank[q]] = mine[q];
+        };
+        if (N <= kThreads) count_sort(std::integral_constant<int, 1>{});
+        else count_sort(std::integral_constant<int, 2>{});
+    } else {
     for (int k = 2; k <= n2; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
             for (int i = tid; i < (n2 >> 1); i += kThreads) {
@@ -53,6 +86,7 @@ __global__ __launch_bounds__(kThreads) void prune_kernel(PruneArgs a, int n2) {
                 __syncthreads();
             }
         }
+    }
 
     __syncthreads();  // the sorted order is read by every wavefront
     // kept flags by original index; sorted values for the prefix sums
