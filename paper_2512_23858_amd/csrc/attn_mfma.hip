@@ -72,7 +72,7 @@ __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& raw, uint4& first8,
 // carry none of its loop state.
 template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false>
 __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
-    static_assert(!BAL || (KS == 1 && !KV8), "balanced batches: plain 32-row wavefronts only");
+    static_assert(!BAL || KS == 1, "balanced batches: plain 32-row wavefronts only");
     static_assert(KS == 1 || (KS == 2 && NW % 2 == 0 && KT == 64), "key shares: one block of the tile each");
     constexpr int NLD = KV8 ? 4 : 0;                             // loading wavefronts (KV8 only)
     constexpr int NSET = 4;                                      // register sets (tiles in flight) per loader
@@ -777,6 +777,10 @@ hipError_t launch_variant(const AttnArgs& a, const AttnPlan& p, hipStream_t st) 
 template <int NW, int RB, int KT, int KS, bool KV8 = false>
 hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     if constexpr (KV8) {
+        if constexpr (KS == 1) {
+            if (a.slots > 0) return launch_variant<NW, RB, KT, KS, true, false, true>(a, p, st);
+        }
+        if (a.slots > 0) return hipErrorInvalidValue;
         return launch_variant<NW, RB, KT, KS, true, false>(a, p, st);  // the loaders' register loads always stream
     } else {
         if constexpr (KS == 1) {
@@ -807,6 +811,7 @@ hipError_t raise_limits_attn_mfma() {
     if (e == hipSuccess) e = raise_variant<2, 1, 64, 2, true, false>();
     if (e == hipSuccess) e = raise_variant<4, 1, 64, 2, true, false>();
     if (e == hipSuccess) e = raise_variant<4, 1, 64, 1, true, false>();
+    if (e == hipSuccess) e = raise_variant<4, 1, 64, 1, true, false, true>();
     return e;
 }
 

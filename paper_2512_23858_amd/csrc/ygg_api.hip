@@ -113,7 +113,7 @@ AttnPlan plan_attention(const ygg_shape& s) {
         // number of splits the key tiles of all sequences are laid end to end and cut into equal runs, one per workgroup
         // of a (kv head, row tile): 256 workgroups in all, each with the same number of tiles whatever the lengths.
         const int64_t streams = (int64_t)s.n_kv_heads * p.row_tiles;
-        if (!kv8 && p.kshares == 1 && s.batch >= 2 && s.batch <= 256 && streams <= 128 && !ns_forced) {
+        if (p.kshares == 1 && s.batch >= 2 && s.batch <= 256 && streams <= 128 && !ns_forced) {
             int64_t slots = 256 / streams;
             const int64_t most = (int64_t)s.batch * tiles;   // never more runs than tiles
             if (slots > most) slots = most;
