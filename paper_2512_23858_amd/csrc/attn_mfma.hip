@@ -117,7 +117,7 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     //             sequence).  Segment number (slot - first slot of the sequence) is the split index of its partials;
     //             nsplit = a.slots bounds it.  A sequence that lies inside one slot is written out directly.
     constexpr bool balanced = BAL;
-    int hk, b_first, b_last, slot = 0, run_lo = 0, run_hi = 0, tiles_all = 0, tiles_before = 0;
+    int hk, b_first, b_last, slot = 0, run_lo = 0, run_hi = 0, tiles_all = 0, tiles_before = 0, nruns = 1;
     if constexpr (!balanced) {
         hk = (sigma / a.nsplit) % a.Hkv;
         b_first = b_last = sigma / (a.nsplit * a.Hkv);
@@ -130,8 +130,11 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
             return (Lb + a.N + kKeyTile - 1) / kKeyTile;
         };
         for (int bb = 0; bb < a.B; ++bb) tiles_all += tiles_of(bb);
-        run_lo = (int)((int64_t)slot * tiles_all / a.slots);
-        run_hi = (int)((int64_t)(slot + 1) * tiles_all / a.slots);
+        // never more runs than tiles (the host sized the grid for the longest lengths the shape allows): every run then
+        // holds a tile, so the runs a sequence falls into are consecutive and its split indices have no gaps
+        nruns = min(a.slots, tiles_all);
+        run_lo = slot < nruns ? (int)((int64_t)slot * tiles_all / nruns) : 0;
+        run_hi = slot < nruns ? (int)((int64_t)(slot + 1) * tiles_all / nruns) : 0;
         // first and last sequence with tiles inside [run_lo, run_hi)
         b_first = 0;
         int acc = 0;
@@ -140,15 +143,15 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
         b_last = b_first;
         acc += tiles_of(b_first);
         while (b_last < a.B - 1 && acc < run_hi) acc += tiles_of(++b_last);
-        if (run_lo >= run_hi) b_last = b_first - 1;  // more slots than tiles: nothing to do
+        if (run_lo >= run_hi) b_last = b_first - 1;  // a workgroup beyond the last run: nothing to do
     }
-    // the slot that holds tile x of the concatenation: the largest s with floor(s * tiles_all / slots) <= x
-    auto slot_of_tile = [&](int x) { return (int)((((int64_t)x + 1) * a.slots - 1) / tiles_all); };
+    // the run that holds tile x of the concatenation: the largest s with floor(s * tiles_all / nruns) <= x
+    auto slot_of_tile = [&](int x) { return (int)((((int64_t)x + 1) * nruns - 1) / tiles_all); };
     // all of this is the same in every lane: keep it in scalar registers (the vector registers are all spoken for)
     auto uni = [](int v) { return __builtin_amdgcn_readfirstlane(v); };
     if constexpr (balanced) {
         hk = uni(hk); b_first = uni(b_first); b_last = uni(b_last); run_lo = uni(run_lo); run_hi = uni(run_hi);
-        tiles_before = uni(tiles_before); tiles_all = uni(tiles_all);
+        tiles_before = uni(tiles_before); tiles_all = uni(tiles_all); nruns = uni(nruns);
     } else {
         b_last = b_first;
     }

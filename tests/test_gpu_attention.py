@@ -86,6 +86,8 @@ RAGGED_BATCHES = [
     (16, 8, 2, 6, 8, [37 * i % 601 for i in range(16)], 640), # many short sequences per run; R = 196
     (7, 32, 4, 5, 6, [511, 512, 513, 1, 1023, 1024, 1025], 1100),   # lengths around tile boundaries; R = 248
     (2, 8, 2, 10, 12, [3000, 100], 3000),                     # R = 484: a sequence whose length equals max_seq_len
+    (6, 16, 4, 8, 12, [38, 13, 16, 23, 2, 21], 50),           # lengths far below the bound: the grid holds more runs than
+                                                              # there are tiles, and sequences of two or three tiles
 ]
 
 
