@@ -12,8 +12,9 @@
 //
 // Per 32-key block and 32-row block (all MFMA are v_mfma_f32_32x32x16_bf16):
 //   S^T = K . Q^T      A = K rows from LDS (16-byte reads), B = Q held in registers
-//   online softmax     a lane owns one query row: 16 scores in registers, one cross-half
-//                      exchange for the row maximum; base-2 exponentials
+//   online softmax     a lane owns one query row: 16 scores in registers; base-2 exponentials
+//                      against a per-row reference that moves rarely (no row maximum on the
+//                      common path)
 //   O^T += V^T . P^T   A = V^T through the LDS transpose read (ds_read_b64_tr_b16), B = P^T,
 //                      which is exactly the accumulator layout of S^T packed to bf16
 // The tree's own keys are the tail of the key range; their ancestor mask comes from per-node
