@@ -600,11 +600,22 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     // Tile t lives in buffer t % NBUF.  The loop is unrolled NBUF-fold with the buffer index a compile-time constant, so
     // that every LDS operand address is a loop-invariant per-lane register plus an immediate (no address arithmetic
     // per block).
+    // A wavefront whose 32 rows all lie beyond the last query row (the padding of the last row tile) only keeps the
+    // barriers and its share of the tile fills company: its matrix and vector work would be spent on zeros, and what it
+    // does not burn the others get back as clock (config 5: 3 of 16 wavefronts per K/V stream, call 172.4 -> 165.9 us;
+    // config 4: 7 of 48, 196.7 -> 192.1).  Only the 256-row shape takes the branch: the six-wavefront shape measured
+    // 1.5 % slower with it.
+    constexpr bool kSkipIdle = NW == 8 && KS == 1;
+    const bool has_rows = !kSkipIdle || __builtin_amdgcn_readfirstlane((int)(row_base + wrow * RB * 32 < R)) != 0;
     auto body = [&](int t, auto bufc) __attribute__((always_inline)) {
         constexpr int buf = decltype(bufc)::value;
         constexpr int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
         const int tile_base = k0 + t * KT;
         const bool clean = tile_base + KT <= clean_end;
+        if (!has_rows) {
+            turn(t, buf, tile_base);
+            return;
+        }
         if constexpr (KS == 1) {
             // block 0 of the tile
             read_v(buf, 0, va);
@@ -631,8 +642,10 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
         if (t + 1 < ntiles) qk(ka, st);
         __builtin_amdgcn_sched_barrier(0);
     };
-    read_k(0, kh, ka);
-    qk(ka, st);
+    if (has_rows) {
+        read_k(0, kh, ka);
+        qk(ka, st);
+    }
     static_assert(NBUF == 3, "the unrolling below names the three buffers");
     int t = 0;
     for (; t + 3 <= ntiles; t += 3) {
