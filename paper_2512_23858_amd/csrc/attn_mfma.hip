@@ -602,11 +602,13 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     // per block).
     // A wavefront whose 32 rows all lie beyond the last query row (the padding of the last row tile) only keeps the
     // barriers and its share of the tile fills company: its matrix and vector work would be spent on zeros, and what it
-    // does not burn the others get back as clock (config 5: 3 of 16 wavefronts per K/V stream, call 172.4 -> 165.9 us;
-    // config 4: 7 of 48, 196.7 -> 192.1).  Only the 256-row shape takes the branch: the six-wavefront shape measured
-    // 1.5 % slower with it.
+    // does not burn the others get back as clock (config 5: 3 of 16 wavefronts per K/V stream, call 172.4 -> 165.9 us).
+    // Wavefronts 0 to 4 always work, so that one SIMD keeps its pair and the workgroup keeps the pace of the other row
+    // tiles of its K/V stream: a workgroup that runs ahead of them fetches every tile from HBM a second time (config 4
+    // with all seven idle wavefronts of its last row tile skipping: 221 MB fetched per launch instead of 149).  Only the
+    // 256-row shape takes the branch: the six-wavefront shape measured 1.5 % slower with it.
     constexpr bool kSkipIdle = NW == 8 && KS == 1;
-    const bool has_rows = !kSkipIdle || __builtin_amdgcn_readfirstlane((int)(row_base + wrow * RB * 32 < R)) != 0;
+    const bool has_rows = !kSkipIdle || wave <= 4 || __builtin_amdgcn_readfirstlane((int)(row_base + wrow * RB * 32 < R)) != 0;
     auto body = [&](int t, auto bufc) __attribute__((always_inline)) {
         constexpr int buf = decltype(bufc)::value;
         constexpr int buf_next = buf + 1 == NBUF ? 0 : buf + 1;
