@@ -80,6 +80,9 @@ def run_config(cid, args, want_cpu):
         hq_, hkv_ = (int(x) for x in args.heads.split(","))
         cfg = wl.scaled(cfg, n_q_heads=hq_, n_kv_heads=hkv_)
         variant += f" with heads {hq_}/{hkv_}"
+    if args.head_dim:
+        cfg = wl.scaled(cfg, head_dim=args.head_dim)
+        variant += f" with head_dim {args.head_dim}"
     if args.prefix:
         cfg = wl.scaled(cfg, prefix_len=args.prefix, prefix_range=())
         variant += f" with prefix {args.prefix}"
@@ -363,6 +366,7 @@ def main():
     ap.add_argument("--attention-only", action="store_true", help="time only the attention calls of a step")
     ap.add_argument("--tree", default="", help="override the tree of the configuration: D,W (N = 1 + D*W nodes)")
     ap.add_argument("--heads", default="", help="override the head counts of the configuration: Hq,Hkv")
+    ap.add_argument("--head-dim", type=int, default=0, choices=[0, 64, 128], help="override the head_dim of the configuration")
     ap.add_argument("--prefix", type=int, default=0, help="override the KV prefix length of the configuration (all sequences)")
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences of the configuration")
     ap.add_argument("--growth", choices=["frontier", "attach"], default="frontier",
@@ -411,7 +415,7 @@ def main():
     # no kernel streams at speed.  The default run therefore adds the same layer shape with 8 sequences x 4096 tokens
     # (550 MB per launch, 49 query rows per kv head: far below the ridge), attention calls only.
     kv_bound = None
-    if not args.config and not (args.tree or args.heads or args.prefix or args.batch or args.plan or args.kv != "native"):
+    if not args.config and not (args.tree or args.heads or args.head_dim or args.prefix or args.batch or args.plan or args.kv != "native"):
         import copy
         a2 = copy.copy(args)
         a2.batch, a2.prefix, a2.layers, a2.attention_only = 8, 4096, 2, True

@@ -19,13 +19,13 @@ typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int DH = 128;
-constexpr int ROWB = 256;  // bytes of one K or V row (head_dim 128, bf16) = 16 slots of 16 bytes
+// One K or V row of head_dim DH in bf16 is ROWB = 2*DH bytes = ROWB/16 slots of 16 bytes (head_dim 128: 16 slots, 64: 8).
 // LDS tiles are filled by direct-to-LDS loads (64 lanes x 16 bytes land contiguously), so rows are
 // unpadded and bank conflicts are avoided by permuting the 16-byte slots inside each row instead:
-//   K tile: slot' = slot ^ (row & 15)         16 consecutive rows read the same column conflict-free
-//   V tile: slot' = slot ^ ((row & 3) << 2)   a transpose read of 32 lanes touches 4 rows x 2 pairs of
-//                                             32 bytes: pair' = pair ^ 2*(row & 3) gives 8 distinct pairs
+//   K tile: slot' = slot ^ (row & (ROWB/16 - 1))       as many consecutive rows as a row has slots read the same
+//                                                      column conflict-free
+//   V tile: slot' = slot ^ ((row & (DH/32 - 1)) << 2)  a transpose read of 32 lanes touches 4 rows x 64 bytes: the
+//                                                      64-byte chunks of neighbouring rows land on different banks
 // The permutation is applied on the global side (which 16 bytes a lane fetches), never in LDS.
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;

@@ -1,4 +1,4 @@
-// Tree-masked verify attention on the gfx950 matrix cores (bf16 storage, head_dim 128).
+// Tree-masked verify attention on the gfx950 matrix cores (bf16 storage, head_dim 128 or 64).
 //
 // Operation (paper Sec. 2 "Source of Improvements", Sec. 4.2 last paragraph): every tree node
 // attends to the confirmed prefix, to its ancestors and to itself, all nodes in one pass.
@@ -71,9 +71,19 @@ __device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& raw, uint4& first8,
 //
 // BAL: balanced batches (see the segment loop below); a separate instantiation, so that the single-segment variants
 // carry none of its loop state.
-template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false>
+//
+// DHT: head_dim, 128 or 64 (bf16 K/V only for 64).  Everything below counts in k-steps of 16 and output blocks of 32
+// head_dim positions, and a direct-to-LDS instruction brings 1024 / ROWB rows.
+template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false, int DHT = 128>
 __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1)) void attn_mfma_kernel(AttnArgs a, int RT, int S) {
     static_assert(!BAL || KS == 1, "balanced batches: plain 32-row wavefronts only");
+    static_assert(DHT == 128 || (DHT == 64 && !KV8), "head_dim 64: bf16 K/V only");
+    constexpr int DH = DHT;
+    constexpr int ROWB = 2 * DH;                                 // bytes of one K or V row in LDS
+    constexpr int NS = DH / 16;                                  // k-steps of S^T = K.Q^T
+    constexpr int NDB = DH / 32;                                 // 32-wide blocks of head_dim in O^T
+    constexpr int SLOTS = ROWB / 16;                             // 16-byte slots per row = lanes that fill one row
+    constexpr int RPI = 1024 / ROWB;                             // rows one direct-to-LDS wave-instruction brings
     static_assert(KS == 1 || (KS == 2 && NW % 2 == 0 && KT == 64), "key shares: one block of the tile each");
     constexpr int NLD = KV8 ? 4 : 0;                             // loading wavefronts (KV8 only)
     constexpr int NSET = 4;                                      // register sets (tiles in flight) per loader
@@ -85,7 +95,8 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     constexpr int NBUF = 3;  // tiles are prefetched two ahead
     // wavefronts that issue tile fills (a power of two, so that each issues the same number per tile)
     constexpr int FILLERS = NW >= 8 ? 8 : NW >= 4 ? 4 : NW >= 2 ? 2 : 1;
-    constexpr int PT = 2 * (KT / 4) / FILLERS;  // direct-to-LDS loads per filling wavefront and tile
+    constexpr int PT = 2 * (KT / RPI) / FILLERS;  // direct-to-LDS loads per filling wavefront and tile
+    static_assert((KT / RPI) % FILLERS == 0, "every filling wavefront issues the same number of loads");
     extern __shared__ __align__(16) unsigned char smem[];
     unsigned char* k_s = smem;                                   // [NBUF][KT][ROWB]
     unsigned char* v_s = smem + NBUF * TILEB;                    // [NBUF][KT][ROWB]
@@ -173,17 +184,17 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
 
     // (issued before the sequence length is first needed: the rows do not depend on it, and the length is a
     // dependent load from device memory at the head of every workgroup's critical path)
-    // Q as the B operand of S^T = K.Q^T: lane (n, g2) holds Q[row n][16 s + 8 g2 .. +8) for s = 0..7
-    bf16x8 qreg[RB][8];
+    // Q as the B operand of S^T = K.Q^T: lane (n, g2) holds Q[row n][16 s + 8 g2 .. +8) for s = 0..NS-1
+    bf16x8 qreg[RB][NS];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         if (rg_of[rb] >= 0) {
             const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const uint16_t*>(a.q) + (int64_t)rg_of[rb] * DH + 8 * g2);
 #pragma unroll
-            for (int s = 0; s < 8; ++s) qreg[rb][s] = qp[2 * s];
+            for (int s = 0; s < NS; ++s) qreg[rb][s] = qp[2 * s];
         } else {
 #pragma unroll
-            for (int s = 0; s < 8; ++s) qreg[rb][s] = bf16x8{};
+            for (int s = 0; s < NS; ++s) qreg[rb][s] = bf16x8{};
         }
     }
 
@@ -248,8 +259,8 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     const unsigned char* kt = uniform_ptr(static_cast<const unsigned char*>(a.k_tree) + ((int64_t)b * a.N * a.Hkv + hk) * (DH * EB));
     const unsigned char* vt = uniform_ptr(static_cast<const unsigned char*>(a.v_tree) + ((int64_t)b * a.N * a.Hkv + hk) * (DH * EB));
 
-    // Direct-to-LDS tile fill: wave-instruction `inst` brings rows 4*inst .. 4*inst+3 of the tile;
-    // lane l lands at byte 1024*inst + 16*l, i.e. row 4*inst + l/16, slot' = l%16, and therefore
+    // Direct-to-LDS tile fill: wave-instruction `inst` brings rows RPI*inst .. RPI*inst+RPI-1 of the tile;
+    // lane l lands at byte 1024*inst + 16*l, i.e. row RPI*inst + l/SLOTS, slot' = l%SLOTS, and therefore
     // fetches the slot that the row's permutation maps there.  Rows past the end of the split fetch
     // the split's last key again: their scores are masked, and their V rows are finite, so that a
     // zero weight times them stays zero.  Every filling wavefront issues exactly PT loads per tile.
@@ -259,14 +270,14 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     // the host checks that a slab stays below 4 GiB.
     const uint32_t tok_bytes = (uint32_t)a.Hkv * DH * EB;
     // per-lane byte offsets of this wavefront's loads inside a tile of cache rows (fast path below)
-    constexpr int FPW = (KT / 4) / FILLERS;  // wave-instructions per filling wavefront, tile and tensor
+    constexpr int FPW = (KT / RPI) / FILLERS;  // wave-instructions per filling wavefront, tile and tensor
     uint32_t fill_k[FPW], fill_v[FPW];
 #pragma unroll
     for (int it = 0; it < FPW; ++it) {
-        const int row = 4 * (wave + it * FILLERS) + (lane >> 4);
-        const int slotp = lane & 15;
-        fill_k[it] = (uint32_t)row * tok_bytes + 16 * (slotp ^ (row & 15));
-        fill_v[it] = (uint32_t)row * tok_bytes + 16 * (slotp ^ ((row & 3) << 2));
+        const int row = RPI * (wave + it * FILLERS) + lane / SLOTS;
+        const int slotp = lane % SLOTS;
+        fill_k[it] = (uint32_t)row * tok_bytes + 16 * (slotp ^ (row & (SLOTS - 1)));
+        fill_v[it] = (uint32_t)row * tok_bytes + 16 * (slotp ^ ((row & (NDB - 1)) << 2));
     }
     auto fill_tile = [&](int buf, int tile_base) {
         if (wave >= FILLERS) return;
@@ -285,23 +296,23 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
 #pragma unroll
         for (int it = 0; it < FPW; ++it) {
             const int inst = wave + it * FILLERS;
-            const int row = 4 * inst + (lane >> 4);
-            const int slotp = lane & 15;
-            const int j0 = tile_base + 4 * inst;     // wave-uniform first key of these four rows
+            const int row = RPI * inst + lane / SLOTS;
+            const int slotp = lane % SLOTS;
+            const int j0 = tile_base + RPI * inst;   // wave-uniform first key of these RPI rows
             const int j = min(tile_base + row, k1 - 1);
-            const uint32_t kcol = 16 * (slotp ^ (row & 15));
-            const uint32_t vcol = 16 * (slotp ^ ((row & 3) << 2));
+            const uint32_t kcol = 16 * (slotp ^ (row & (SLOTS - 1)));
+            const uint32_t vcol = 16 * (slotp ^ ((row & (NDB - 1)) << 2));
             const uint32_t kdst = __builtin_amdgcn_readfirstlane(kdst0 + it * FILLERS * 1024);
             const uint32_t vdst = __builtin_amdgcn_readfirstlane(vdst0 + it * FILLERS * 1024);
-            if (j0 + 4 <= L) {                       // four cache rows (uniform branch)
+            if (j0 + RPI <= L) {                     // cache rows only (uniform branch)
                 const uint32_t off = (uint32_t)j * tok_bytes;
                 dma_load16<NT>(kc, off + kcol, kdst);
                 dma_load16<NT>(vc, off + vcol, vdst);
-            } else if (j0 >= L) {                    // four tree rows
+            } else if (j0 >= L) {                    // tree rows only
                 const uint32_t off = (uint32_t)(j - L) * tok_bytes;
                 dma_load16<NT>(kt, off + kcol, kdst);
                 dma_load16<NT>(vt, off + vcol, vdst);
-            } else {                                 // the four rows straddle the end of the prefix
+            } else {                                 // the rows straddle the end of the prefix
                 const bool in_cache = j < L;
                 const uint32_t off = (uint32_t)(in_cache ? j : j - L) * tok_bytes;
                 const void* kb = in_cache ? (const void*)kc : (const void*)kt;
@@ -368,14 +379,14 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
         }
     };
 
-    f32x16 o[RB][4];
+    f32x16 o[RB][NDB];
     float m_ref[RB], l_run[RB];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb) {
         m_ref[rb] = -INFINITY;
         l_run[rb] = 0.f;
 #pragma unroll
-        for (int db = 0; db < 4; ++db) o[rb][db] = f32x16{};
+        for (int db = 0; db < NDB; ++db) o[rb][db] = f32x16{};
     }
     // KV8: K = k_scale * code value, so the scale (positive) joins the softmax scale
     const float c_scale = a.scale * kLog2e * (KV8 ? a.k_scale[hk] : 1.f);
@@ -393,26 +404,26 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     // reference underflow to weight 0, which is what they are worth next to the key that set it.  The
     // result O / l and lse = m_ref ln 2 + ln l do not depend on the reference.
     const int j16 = lane & 15;
-    // K operand of step s: row n, slot 2s+g2 -> slot' = (2s+g2) ^ (n&15) = 2*(s ^ (n&15)>>1) + (g2 ^ (n&1))
+    // K operand of step s: row n, slot 2s+g2 -> slot' = (2s+g2) ^ (n % SLOTS) = 2*(s ^ (n % SLOTS)>>1) + (g2 ^ (n&1))
     const int k_lane_off = n * ROWB + 16 * (g2 ^ (n & 1));
-    const int k_pair_xor = ((n & 15) >> 1) << 5;
-    // V operand: row z = 4*g2 + j16/4 (+ multiples of 8), 32-byte pair 2*db + (lane/16)%2 -> pair' = pair ^ 2*(z&3)
+    const int k_pair_xor = ((n & (SLOTS - 1)) >> 1) << 5;
+    // V operand: row z = 4*g2 + j16/4 (+ multiples of 8), 32-byte pair 2*db + (lane/16)%2 -> pair' = pair ^ 2*(z % NDB)
     const int v_z = 4 * g2 + (j16 >> 2);
     const int v_lane_off = v_z * ROWB + 8 * (j16 & 3);
     const int v_pair = (lane >> 4) & 1;
-    const int v_px = (v_z & 3) << 1;
+    const int v_px = (v_z & (NDB - 1)) << 1;
 
-    auto read_k = [&](int buf, int kb, bf16x8 (&ka)[8]) {
+    auto read_k = [&](int buf, int kb, bf16x8 (&ka)[NS]) {
         const unsigned char* kbuf = k_s + buf * TILEB + kb * 32 * ROWB + k_lane_off;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) ka[s] = *reinterpret_cast<const bf16x8*>(kbuf + ((32 * s) ^ k_pair_xor));
+        for (int s = 0; s < NS; ++s) ka[s] = *reinterpret_cast<const bf16x8*>(kbuf + ((32 * s) ^ k_pair_xor));
     };
     // lane j of a 16-lane group addresses key row (j/4), dh 4*(j%4); the transpose read hands each
     // lane four keys of one dh, i.e. the A operand of O^T += V^T.P^T
-    auto read_v = [&](int buf, int kb, i16x8 (&va)[4][2]) {
+    auto read_v = [&](int buf, int kb, i16x8 (&va)[NDB][2]) {
         const unsigned char* vbuf = v_s + buf * TILEB + kb * 32 * ROWB + v_lane_off;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int m2 = 0; m2 < 2; ++m2) {
                 const unsigned char* p = vbuf + (16 * m2) * ROWB + 32 * ((2 * db + v_pair) ^ v_px);
@@ -421,20 +432,20 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 va[db][m2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
     };
-    auto qk = [&](const bf16x8 (&ka)[8], f32x16 (&st)[RB]) {
+    auto qk = [&](const bf16x8 (&ka)[NS], f32x16 (&st)[RB]) {
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) st[rb] = f32x16{};
 #pragma unroll
-        for (int s = 0; s < 8; ++s)
+        for (int s = 0; s < NS; ++s)
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
                 st[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[rb][s], st[rb], 0, 0, 0);
     };
-    auto pv = [&](const i16x8 (&va)[4][2], const i16x8 (&pb)[RB][2]) {
+    auto pv = [&](const i16x8 (&va)[NDB][2], const i16x8 (&pb)[RB][2]) {
 #pragma unroll
         for (int m2 = 0; m2 < 2; ++m2)
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
                     o[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
@@ -501,7 +512,7 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                 if (raise) m_ref[rb] = row_max;
                 l_run[rb] *= alpha;
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
+                for (int db = 0; db < NDB; ++db)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[rb][db][v] *= alpha;
                 ps = weights(m_ref[rb] == -INFINITY ? 0.f : m_ref[rb]);  // the scores are still in st
@@ -593,8 +604,8 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     };
 
     // One barrier per tile (inside turn).
-    bf16x8 ka[8];
-    i16x8 va[4][2];
+    bf16x8 ka[NS];
+    i16x8 va[NDB][2];
     f32x16 st[RB];
     i16x8 pb[RB][2];
     // Tile t lives in buffer t % NBUF.  The loop is unrolled NBUF-fold with the buffer index a compile-time constant, so
@@ -663,26 +674,27 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
         // Merge of the two key shares of a row block.  Both carry O~ and l relative to their own
         // reference m_ref; the share of block 1 hands its state over through the (now idle) tile
         // buffers, lane for lane, and the share of block 0 rescales both to the larger reference.
-        float* xch = reinterpret_cast<float*>(smem) + wrow * (RB * 66 * 64) + lane;  // [wrow][rb][66][64 lanes]
+        constexpr int XR = 16 * NDB + 2;  // a lane's accumulators, then m and l
+        float* xch = reinterpret_cast<float*>(smem) + wrow * (RB * XR * 64) + lane;  // [wrow][rb][XR][64 lanes]
         __syncthreads();  // every wavefront is done with the tiles
         if (kh == 1) {
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb) {
-                float* x = xch + rb * 66 * 64;
+                float* x = xch + rb * XR * 64;
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
+                for (int db = 0; db < NDB; ++db)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) x[(16 * db + v) * 64] = o[rb][db][v];
-                x[64 * 64] = m_ref[rb];
-                x[65 * 64] = l_run[rb];
+                x[(XR - 2) * 64] = m_ref[rb];
+                x[(XR - 1) * 64] = l_run[rb];
             }
         }
         __syncthreads();
         if (kh == 1) return;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb) {
-            const float* x = xch + rb * 66 * 64;
-            const float m1 = x[64 * 64], l1 = x[65 * 64];
+            const float* x = xch + rb * XR * 64;
+            const float m1 = x[(XR - 2) * 64], l1 = x[(XR - 1) * 64];
             const float mm = fmaxf(m_ref[rb], m1);
             // a share that saw no visible key has m = -inf, l = 0, O~ = 0: weight 0 keeps it out
             const float w0 = m_ref[rb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_ref[rb] - mm);
@@ -690,7 +702,7 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
             m_ref[rb] = mm;
             l_run[rb] = l_run[rb] * w0 + l1 * w1;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o[rb][db][v] = o[rb][db][v] * w0 + x[(16 * db + v) * 64] * w1;
         }
@@ -706,7 +718,7 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
             const float inv = v_unit / l_tot;
             uint16_t* op = static_cast<uint16_t*>(a.out) + (int64_t)rg_of[rb] * DH + 4 * g2;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
                     uint2 w;
@@ -723,7 +735,7 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
             // and leaving them dirty in L2 only lengthens the write-back at the end of this kernel.
             float rmax = 0.f;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, fabsf(o[rb][db][v]));
             rmax = fmaxf(rmax, __shfl_xor(rmax, 32));
@@ -732,9 +744,9 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
             // The two lanes of a row hold alternating groups of four head_dim positions; swapping halves between them
             // (v_permlane32_swap) leaves each with eight consecutive ones, so a store covers 32 contiguous bytes of a row.
             _Float16* po = reinterpret_cast<_Float16*>(a.part_o) + ((int64_t)split * rows_total + rg_of[rb]) * DH + 8 * g2;
-            u32x4 w[4][2];
+            u32x4 w[NDB][2];
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int vp = 0; vp < 2; ++vp) {
                     const f32x4 ve = {o[rb][db][8 * vp] * inv_c, o[rb][db][8 * vp + 1] * inv_c,
@@ -747,10 +759,10 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
                     const auto s1 = __builtin_amdgcn_permlane32_swap(he[1], ho[1], false, false);
                     w[db][vp] = u32x4{s0[0], s1[0], s0[1], s1[1]};
                 }
-            // the eight stores of a row leave back to back: neighbouring 32-byte pieces then combine into whole lines
+            // the stores of a row leave back to back: neighbouring 32-byte pieces then combine into whole lines
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int vp = 0; vp < 2; ++vp)
                     __builtin_nontemporal_store(w[db][vp], reinterpret_cast<u32x4*>(po + 32 * db + 16 * vp));
@@ -767,17 +779,17 @@ __global__ __launch_bounds__((NW + (KV8 ? 4 : 0)) * 64, (RB == 1 && !KV8 ? 2 : 1
     }      // segments of this workgroup
 }
 
-// Largest dynamic shared memory any shape asks for: six 16 KiB tiles, ancestor masks of up to 257 nodes x 32 words, and
-// the parent table of 1024 nodes.  Every variant's limit is raised to it once per device.
-constexpr size_t kMaxSmem = (size_t)2 * 3 * 64 * ROWB + (size_t)257 * 32 * 4 + 1024 * 4;
+// Largest dynamic shared memory any shape asks for: six 16 KiB tiles (head_dim 128), ancestor masks of up to 257 nodes x
+// 32 words, and the parent table of 1024 nodes.  Every variant's limit is raised to it once per device.
+constexpr size_t kMaxSmem = (size_t)2 * 3 * 64 * 256 + (size_t)257 * 32 * 4 + 1024 * 4;
 
-template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false>
+template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false, int DHT = 128>
 hipError_t raise_variant() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<NW, RB, KT, KS, KV8, NT, BAL>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(attn_mfma_kernel<NW, RB, KT, KS, KV8, NT, BAL, DHT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxSmem);
 }
 
-template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false>
+template <int NW, int RB, int KT, int KS, bool KV8, bool NT, bool BAL = false, int DHT = 128>
 hipError_t launch_variant(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     const int S = a.slots > 0 ? a.Hkv * a.slots : a.B * a.Hkv * a.nsplit;   // K/V streams, each read by RT workgroups
     const int RT = p.row_tiles;
@@ -785,15 +797,16 @@ hipError_t launch_variant(const AttnArgs& a, const AttnPlan& p, hipStream_t st) 
     const int RW = NW / KS * RB * 32;
     const int nodes_local = (RW + a.G - 1) / a.G + 1;
     // three K and three V tile buffers, the ancestor bitmasks and the parent table
-    const size_t smem = (size_t)2 * 3 * KT * ROWB + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
-    auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8, NT, BAL>;
+    const size_t smem = (size_t)2 * 3 * KT * (2 * DHT) + (size_t)nodes_local * ((a.N + 31) / 32) * 4 + (size_t)a.N * 4;
+    auto kern = attn_mfma_kernel<NW, RB, KT, KS, KV8, NT, BAL, DHT>;
     const unsigned threads = (NW + (KV8 ? 4 : 0)) * 64;  // KV8: plus the four loading wavefronts
+    if (a.Dh != DHT) return hipErrorInvalidValue;
     if (smem > kMaxSmem) return hipErrorInvalidValue;  // cannot happen for N <= 1024: checked again for the sake of the launch
     hipLaunchKernelGGL(kern, dim3((unsigned)(S8 * RT)), dim3(threads), smem, st, a, RT, S);
     return hipGetLastError();
 }
 
-template <int NW, int RB, int KT, int KS, bool KV8 = false>
+template <int NW, int RB, int KT, int KS, bool KV8 = false, int DHT = 128>
 hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     if constexpr (KV8) {
         if constexpr (KS == 1) {
@@ -804,29 +817,50 @@ hipError_t launch_cfg(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     } else {
         if constexpr (KS == 1) {
             if (a.slots > 0)
-                return p.row_tiles == 1 ? launch_variant<NW, RB, KT, KS, false, true, true>(a, p, st)
-                                        : launch_variant<NW, RB, KT, KS, false, false, true>(a, p, st);
+                return p.row_tiles == 1 ? launch_variant<NW, RB, KT, KS, false, true, true, DHT>(a, p, st)
+                                        : launch_variant<NW, RB, KT, KS, false, false, true, DHT>(a, p, st);
         }
         if (a.slots > 0) return hipErrorInvalidValue;
-        return p.row_tiles == 1 ? launch_variant<NW, RB, KT, KS, false, true>(a, p, st)
-                                : launch_variant<NW, RB, KT, KS, false, false>(a, p, st);
+        return p.row_tiles == 1 ? launch_variant<NW, RB, KT, KS, false, true, false, DHT>(a, p, st)
+                                : launch_variant<NW, RB, KT, KS, false, false, false, DHT>(a, p, st);
     }
+}
+
+// the six workgroup shapes of the bf16 kernel for one head_dim
+template <int DHT>
+hipError_t launch_shape(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
+    switch (p.waves * 10 + p.kshares) {
+        case 41: return launch_cfg<4, 1, 64, 1, false, DHT>(a, p, st);
+        case 61: return launch_cfg<6, 1, 64, 1, false, DHT>(a, p, st);
+        case 81: return launch_cfg<8, 1, 64, 1, false, DHT>(a, p, st);
+        case 22: return launch_cfg<2, 1, 64, 2, false, DHT>(a, p, st);
+        case 42: return launch_cfg<4, 1, 64, 2, false, DHT>(a, p, st);
+        case 82: return launch_cfg<8, 1, 64, 2, false, DHT>(a, p, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int DHT>
+hipError_t raise_shapes() {
+    hipError_t e = hipSuccess;
+    auto both = [&](auto nw, auto ks) {
+        if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, false, false, DHT>();
+        if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, true, false, DHT>();
+        if constexpr (decltype(ks)::value == 1) {
+            if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, 1, false, false, true, DHT>();
+            if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, 1, false, true, true, DHT>();
+        }
+    };
+    both(IntC<4>{}, IntC<1>{}); both(IntC<6>{}, IntC<1>{}); both(IntC<8>{}, IntC<1>{});
+    both(IntC<2>{}, IntC<2>{}); both(IntC<4>{}, IntC<2>{}); both(IntC<8>{}, IntC<2>{});
+    return e;
 }
 
 }  // namespace
 
 hipError_t raise_limits_attn_mfma() {
-    hipError_t e = hipSuccess;
-    auto both = [&](auto nw, auto ks) {
-        if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, false>();
-        if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, decltype(ks)::value, false, true>();
-        if constexpr (decltype(ks)::value == 1) {
-            if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, 1, false, false, true>();
-            if (e == hipSuccess) e = raise_variant<decltype(nw)::value, 1, 64, 1, false, true, true>();
-        }
-    };
-    both(IntC<4>{}, IntC<1>{}); both(IntC<6>{}, IntC<1>{}); both(IntC<8>{}, IntC<1>{});
-    both(IntC<2>{}, IntC<2>{}); both(IntC<4>{}, IntC<2>{}); both(IntC<8>{}, IntC<2>{});
+    hipError_t e = raise_shapes<128>();
+    if (e == hipSuccess) e = raise_shapes<64>();
     if (e == hipSuccess) e = raise_variant<2, 1, 64, 2, true, false>();
     if (e == hipSuccess) e = raise_variant<4, 1, 64, 2, true, false>();
     if (e == hipSuccess) e = raise_variant<4, 1, 64, 1, true, false>();
@@ -836,8 +870,8 @@ hipError_t raise_limits_attn_mfma() {
 
 hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st) {
     if (p.rblocks != 1) return hipErrorInvalidValue;
-    if (a.k_scale || a.v_scale) {  // K/V held as E4M3 codes
-        if (!a.k_scale || !a.v_scale) return hipErrorInvalidValue;
+    if (a.k_scale || a.v_scale) {  // K/V held as E4M3 codes (head_dim 128)
+        if (!a.k_scale || !a.v_scale || a.Dh != 128) return hipErrorInvalidValue;
         switch (p.waves * 10 + p.kshares) {  // computing wavefronts; four loaders on top
             case 22: return launch_cfg<2, 1, 64, 2, true>(a, p, st);
             case 42: return launch_cfg<4, 1, 64, 2, true>(a, p, st);
@@ -845,15 +879,9 @@ hipError_t launch_attn_mfma(const AttnArgs& a, const AttnPlan& p, hipStream_t st
             default: return hipErrorInvalidValue;
         }
     }
-    switch (p.waves * 10 + p.kshares) {
-        case 41: return launch_cfg<4, 1, 64, 1>(a, p, st);
-        case 61: return launch_cfg<6, 1, 64, 1>(a, p, st);
-        case 81: return launch_cfg<8, 1, 64, 1>(a, p, st);
-        case 22: return launch_cfg<2, 1, 64, 2>(a, p, st);
-        case 42: return launch_cfg<4, 1, 64, 2>(a, p, st);
-        case 82: return launch_cfg<8, 1, 64, 2>(a, p, st);
-        default: return hipErrorInvalidValue;
-    }
+    if (a.Dh == 128) return launch_shape<128>(a, p, st);
+    if (a.Dh == 64) return launch_shape<64>(a, p, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace ygg

@@ -275,8 +275,8 @@ hipError_t launch_combine_t(const AttnArgs& a, hipStream_t st) {
         else hipLaunchKernelGGL((attn_combine_kernel<T, 128, false>), grid, dim3(256), 0, st, a);
     } else {
         dim3 grid((unsigned)((rows + 15) / 16));
-        if (a.part_half) return hipErrorInvalidValue;  // the matrix-core kernels exist for head_dim 128 only
-        hipLaunchKernelGGL((attn_combine_kernel<T, 64, false>), grid, dim3(256), 0, st, a);
+        if (a.part_half) hipLaunchKernelGGL((attn_combine_kernel<T, 64, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((attn_combine_kernel<T, 64, false>), grid, dim3(256), 0, st, a);
     }
     return hipGetLastError();
 }

@@ -66,7 +66,7 @@ AttnPlan plan_attention(const ygg_shape& s) {
     const int64_t tiles = (T + kKeyTile - 1) / kKeyTile;
     int64_t ns;
     const bool kv8 = s.kv_dtype == YGG_FP8_E4M3;  // K/V as 8-bit codes, Q and O bf16 (head_dim 128 only)
-    p.use_mfma = (s.kv_dtype == YGG_BF16 || kv8) && s.head_dim == 128;
+    p.use_mfma = (s.kv_dtype == YGG_BF16 && (s.head_dim == 128 || s.head_dim == 64)) || (kv8 && s.head_dim == 128);
     if (p.use_mfma) {
         // query rows that share one K/V stream, and the workgroup shape that wastes the fewest of them
         const int R = s.n_nodes * (s.n_q_heads / s.n_kv_heads);

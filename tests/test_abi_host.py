@@ -235,6 +235,12 @@ def test_attention_plans_of_the_five_configurations():
     per_row = 128 * 2 + 12 if p["matrix_cores"] else (128 + 2) * 4
     need = p["key_splits"] * rows * per_row
     assert need <= ygg.workspace_bytes(s2, ygg.OP_ATTENTION) < need + 3 * 256
+    # head_dim 64 in bf16 runs on the matrix cores too (fp32 storage stays on the vector path)
+    s3 = _shape(head_dim=64, max_seq_len=4096, kv_capacity=4200)
+    p3 = ygg.attention_plan(s3)
+    assert p3["matrix_cores"] and not ygg.attention_plan(_shape(head_dim=64, kv_dtype=0))["matrix_cores"]
+    need = p3["key_splits"] * rows * (64 * 2 + 12)
+    assert need <= ygg.workspace_bytes(s3, ygg.OP_ATTENTION) < need + 3 * 256
 
 
 def test_plan_override_is_explicit_and_removable():

@@ -44,7 +44,13 @@ def _check(cfg, host, parent, max_len, n_nodes=None, depth=None):
         assert err.max() <= 1e-5, err.max()
         assert np.abs(lse - ref_lse).max() <= 1e-5
     else:
-        assert err.max() <= 2e-2 and err.mean() <= 1e-2, (err.max(), err.mean())
+        # 2e-2 everywhere, except where that is less than one bf16 unit in the last place of the exact value (2^-7 of it
+        # at most, i.e. for outputs above 2.56): the output is stored in bf16 (half a unit) and so are the softmax weights
+        # (a quarter more when one key holds all the mass).  N(0,1) values average far below that; only the tree-heavy
+        # cases, whose rows copy single V rows, can reach it.
+        bound = np.maximum(2e-2, 2.0 ** -7 * np.abs(ref_out))
+        worst = np.unravel_index(np.argmax(err - bound), err.shape)
+        assert (err <= bound).all() and err.mean() <= 1e-2, (err[worst], ref_out[worst], out[worst], err.mean())
         rms = np.sqrt((ref_out ** 2).mean())
         assert np.sqrt((err ** 2).mean()) <= 0.02 * rms, (np.sqrt((err ** 2).mean()), rms)
         assert np.abs(lse - ref_lse).max() <= 1e-3, np.abs(lse - ref_lse).max()
@@ -163,9 +169,36 @@ def test_fp32_shapes(case):
     _check(cfg, host, parent, max_len)
 
 
-def test_bf16_head_dim_64_uses_vector_path():
-    cfg, host, parent = _inputs(_cfg(1, 4, 2, 3, 4, Dh=64, seed=95), [90], 90)
-    _check(cfg, host, parent, 90)
+# head_dim 64 on the matrix cores: every workgroup shape (by query rows per kv head), classic key splits and balanced runs,
+# an empty prefix, a partial last tile.  (B, Hq, Hkv, D, W, lens, max_len)
+BF16_HEAD_DIM_64 = [
+    (1, 4, 2, 3, 4, [90], 90),                                # R = 26: two wavefronts in a pair
+    (2, 8, 8, 6, 8, [300, 1], 300),                           # R = 49: four wavefronts in pairs, ragged batch
+    (1, 8, 2, 4, 6, [130], 130),                              # R = 100: eight wavefronts in pairs
+    (1, 12, 2, 5, 5, [1500], 1500),                           # R = 156: 192-row shape, several key splits, partial last tile
+    (1, 16, 2, 5, 6, [257], 257),                             # R = 248: 256-row shape
+    (1, 4, 1, 10, 15, [0], 1),                                # R = 604: three row tiles, tree keys only
+    (1, 12, 12, 8, 8, [2048], 2048),                          # a draft-model-sized layer (12 heads of 64), 8 x 8 tree
+    (5, 16, 2, 6, 8, [900, 0, 64, 1500, 333], 1500),          # balanced runs, R = 392
+    (6, 16, 4, 8, 12, [38, 13, 16, 23, 2, 21], 50),           # balanced runs, more runs than tiles
+    (1, 2, 2, 33, 31, [100], 100),                            # N = 1024
+]
+
+
+@pytest.mark.parametrize("case", BF16_HEAD_DIM_64, ids=lambda c: f"B{c[0]}_Hq{c[1]}_Hkv{c[2]}_D{c[3]}W{c[4]}_L{max(c[5])}")
+@pytest.mark.parametrize("gain", [1.0, 4.0])
+def test_bf16_head_dim_64_shapes(case, gain):
+    import paper_2512_23858_amd as ygg
+    B, Hq, Hkv, D, W, lens, max_len = case
+    cfg, host, parent = _inputs(_cfg(B, Hq, Hkv, D, W, Dh=64, seed=95), lens, max_len, tree_gain=gain)
+    assert ygg.attention_plan(shape_of(cfg, max_seq_len=int(max_len)))["matrix_cores"]
+    _check(cfg, host, parent, max_len)
+
+
+@pytest.mark.parametrize("L", [0, 1, 31, 32, 33, 63, 64, 65])
+def test_bf16_head_dim_64_short_prefix(L):
+    cfg, host, parent = _inputs(_cfg(1, 8, 2, 5, 7, Dh=64, seed=96), [L], max(L, 1), tree_gain=4.0)
+    _check(cfg, host, parent, max(L, 1))
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])

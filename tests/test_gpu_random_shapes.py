@@ -33,7 +33,7 @@ def test_random_attention_shapes(n_cases=120):
         maxL = int(rng.choice([0, 1, 50, 64, 200, 777, 2000, 5000]))
         lens = [int(rng.integers(0, maxL + 1)) for _ in range(B)]
         dtype = "bf16" if rng.random() < 0.8 else "f32"
-        Dh = 128 if dtype == "bf16" or rng.random() < 0.5 else 64
+        Dh = 128 if rng.random() < (0.7 if dtype == "bf16" else 0.5) else 64
         cfg = wl.Config("case", B, Hq, Hkv, Dh, dtype, max(maxL, 1), (), D, W, 100, (0.5,), "dirichlet", 0.5, 1, 1000 + it)
         la = np.asarray(lens, np.int32)
         host = wl.attention_inputs(cfg, lens=la)
